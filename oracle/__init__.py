@@ -1,0 +1,173 @@
+"""ctypes access to the CPU oracle (oracle/wash_ref.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+CPU-baseline leg of bench.py.  The product package never imports this.
+All arrays are host numpy arrays; nothing here touches a GPU.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_LIB = None
+MAX_N = 32
+
+
+class Segment(ctypes.Structure):
+    _fields_ = [("offset", ctypes.c_uint64), ("length", ctypes.c_uint64), ("p", ctypes.c_double)]
+
+
+def lib():
+    global _LIB
+    if _LIB is None:
+        path = _build.build(force=False)
+        L = ctypes.CDLL(path)
+        u32, u64, dbl = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_double
+        vp = ctypes.c_void_p
+        L.wash_ref_philox4x32_10.argtypes = [vp, vp, vp]
+        L.wash_ref_philox4x32_10.restype = None
+        L.wash_ref_threshold.argtypes = [dbl]
+        L.wash_ref_threshold.restype = u64
+        L.wash_ref_mask_word.argtypes = [u64, u64, u64]
+        L.wash_ref_mask_word.restype = u32
+        L.wash_ref_perm_words.argtypes = [u64, u64, u64, u32, vp]
+        L.wash_ref_perm_words.restype = None
+        L.wash_ref_fisher_yates.argtypes = [vp, u32, vp]
+        L.wash_ref_fisher_yates.restype = None
+        L.wash_ref_permutation.argtypes = [u64, u64, u64, u32, vp]
+        L.wash_ref_permutation.restype = ctypes.c_int
+        L.wash_layer_probs_ref.argtypes = [dbl, u32, ctypes.c_int, vp]
+        L.wash_layer_probs_ref.restype = ctypes.c_int
+        L.wash_shuffle_ref_window.argtypes = [vp, vp, u32, u64, u64, u64, u64, vp, u32, u64, u64, vp]
+        L.wash_shuffle_ref_window.restype = ctypes.c_int
+        L.wash_shuffle_ref.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp]
+        L.wash_shuffle_ref.restype = ctypes.c_int
+        L.wash_shuffle_ref_mt.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp, u32]
+        L.wash_shuffle_ref_mt.restype = ctypes.c_int
+        L.wash_average_ref.argtypes = [vp, vp, u32, u64]
+        L.wash_average_ref.restype = ctypes.c_int
+        L.papa_ema_ref.argtypes = [vp, u32, u64, ctypes.c_float]
+        L.papa_ema_ref.restype = ctypes.c_int
+        _LIB = L
+    return _LIB
+
+
+def _segarray(segs):
+    arr = (Segment * max(len(segs), 1))()
+    for k, (off, length, p) in enumerate(segs):
+        arr[k].offset, arr[k].length, arr[k].p = int(off), int(length), float(p)
+    return arr
+
+
+def _check_pop(a, name):
+    if not (isinstance(a, np.ndarray) and a.dtype == np.float32 and a.ndim == 2 and a.flags.c_contiguous):
+        raise TypeError(f"{name}: need a C-contiguous float32 [N, P] numpy array")
+
+
+def philox(ctr, key):
+    c = np.asarray(ctr, dtype=np.uint32).copy()
+    k = np.asarray(key, dtype=np.uint32).copy()
+    o = np.zeros(4, dtype=np.uint32)
+    lib().wash_ref_philox4x32_10(c.ctypes.data, k.ctypes.data, o.ctypes.data)
+    return tuple(int(v) for v in o)
+
+
+def threshold(p):
+    return int(lib().wash_ref_threshold(float(p)))
+
+
+def mask_word(seed, step, g):
+    return int(lib().wash_ref_mask_word(seed, step, g))
+
+
+def perm_words(seed, step, g, N):
+    w = np.zeros(max(N - 1, 1), dtype=np.uint32)
+    lib().wash_ref_perm_words(seed, step, g, N, w.ctypes.data)
+    return w[: N - 1]
+
+
+def fisher_yates(words, N):
+    w = np.ascontiguousarray(np.asarray(words, dtype=np.uint32))
+    if w.size < N - 1:
+        raise ValueError("need N-1 words")
+    w = np.concatenate([w, np.zeros(1, np.uint32)])
+    perm = np.zeros(N, dtype=np.uint32)
+    lib().wash_ref_fisher_yates(w.ctypes.data, N, perm.ctypes.data)
+    return perm
+
+
+def permutation(seed, step, g, N):
+    perm = np.zeros(N, dtype=np.uint32)
+    rc = lib().wash_ref_permutation(seed, step, g, N, perm.ctypes.data)
+    if rc != 0:
+        raise ValueError("wash_ref_permutation failed")
+    return perm
+
+
+def layer_probs(p, L, schedule=0):
+    out = np.zeros(max(L, 1), dtype=np.float64)
+    rc = lib().wash_layer_probs_ref(float(p), int(L), int(schedule), out.ctypes.data)
+    if rc != 0:
+        raise ValueError("wash_layer_probs_ref: invalid argument")
+    return out[:L]
+
+
+def shuffle(params, momentum, segs, seed, step, threads=1):
+    """In-place shuffle of a whole [N, P] population. Returns the selected count."""
+    _check_pop(params, "params")
+    N, P = params.shape
+    if momentum is not None:
+        _check_pop(momentum, "momentum")
+        assert momentum.shape == params.shape
+    sa = _segarray(segs)
+    cnt = ctypes.c_uint64(0)
+    mom = momentum.ctypes.data if momentum is not None else None
+    if threads <= 1:
+        rc = lib().wash_shuffle_ref(params.ctypes.data, mom, N, P, ctypes.addressof(sa), len(segs),
+                                    seed, step, ctypes.addressof(cnt))
+    else:
+        rc = lib().wash_shuffle_ref_mt(params.ctypes.data, mom, N, P, ctypes.addressof(sa), len(segs),
+                                       seed, step, ctypes.addressof(cnt), threads)
+    if rc != 0:
+        raise ValueError(f"wash_shuffle_ref: invalid argument (rc={rc})")
+    return cnt.value
+
+
+def shuffle_window(win, mom_win, P, g_begin, segs, seed, step):
+    """In-place shuffle of a window holding columns [g_begin, g_begin + W) of a
+    population with P columns; win is a contiguous [N, W] array."""
+    _check_pop(win, "win")
+    N, W = win.shape
+    if mom_win is not None:
+        _check_pop(mom_win, "mom_win")
+        assert mom_win.shape == win.shape
+    sa = _segarray(segs)
+    cnt = ctypes.c_uint64(0)
+    mom = mom_win.ctypes.data if mom_win is not None else None
+    rc = lib().wash_shuffle_ref_window(win.ctypes.data, mom, N, P, W, g_begin, g_begin + W,
+                                       ctypes.addressof(sa), len(segs), seed, step, ctypes.addressof(cnt))
+    if rc != 0:
+        raise ValueError(f"wash_shuffle_ref_window: invalid argument (rc={rc})")
+    return cnt.value
+
+
+def average(params):
+    _check_pop(params, "params")
+    N, P = params.shape
+    out = np.empty(P, dtype=np.float32)
+    rc = lib().wash_average_ref(params.ctypes.data, out.ctypes.data, N, P)
+    if rc != 0:
+        raise ValueError("wash_average_ref: invalid argument")
+    return out
+
+
+def ema(params, alpha):
+    """In-place PAPA EMA of a whole [N, P] population."""
+    _check_pop(params, "params")
+    N, P = params.shape
+    rc = lib().papa_ema_ref(params.ctypes.data, N, P, float(alpha))
+    if rc != 0:
+        raise ValueError("papa_ema_ref: invalid argument")
+    return params
