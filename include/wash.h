@@ -1,0 +1,150 @@
+/*
+ * wash.h -- C ABI of the MI355X (gfx950) population-update library for WASH
+ * ("Train your Ensemble with Communication-Efficient Weight Shuffling, then
+ * Average", arXiv 2405.17517).
+ *
+ * The population of N models lives on ONE GPU as a stacked, row-major [N, P]
+ * fp32 buffer (row n = all parameters of model n, tensors concatenated without
+ * padding; row stride = P elements), optionally with a second [N, P] buffer of
+ * optimizer state (SGD momentum).  Three operations act on it:
+ *
+ *   wash_shuffle   the shuffling step            (Sec. 3, Eq. 3; Alg. 1, shuffling step)
+ *   wash_average   the final uniform average     (Alg. 1, output line)
+ *   papa_ema       PAPA's EMA toward the mean    (Sec. 3, Eq. 1)  -- comparison baseline
+ *
+ * and one host helper gives the layer-wise probabilities of Eq. 6.
+ *
+ * Conventions for every entry point
+ *   - "device" pointers are HIP device memory on the CURRENT device of the
+ *     calling thread; "host" pointers are ordinary process memory.
+ *   - The caller owns every buffer it passes.  The library allocates only a
+ *     small internal device table per distinct segment list (cached, released
+ *     by wash_shutdown()).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work on it and return without waiting; the usual stream
+ *     ordering applies to the buffers.
+ *   - Return value: WASH_OK (0) or a negative wash_status.  Arguments are
+ *     validated before anything is launched: on WASH_EINVAL nothing was
+ *     modified.  Nothing throws or aborts.  wash_strerror() gives the text,
+ *     wash_last_error_detail() the detail of the calling thread's last error.
+ */
+#ifndef WASH_H
+#define WASH_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define WASH_MAX_N 32u /* largest population size accepted */
+
+typedef enum wash_status {
+    WASH_OK = 0,
+    WASH_EINVAL = -1, /* an argument violates the contract below */
+    WASH_EHIP = -2,   /* a HIP call (launch, copy, allocation) failed */
+    WASH_ENOMEM = -3  /* host allocation failed */
+} wash_status;
+
+/*
+ * One tensor ("layer" in the sense of Eq. 6 is the caller's business: the
+ * library takes one probability per segment).  Coordinates are positions in a
+ * row, 0 <= offset, offset + length <= P.
+ */
+typedef struct wash_segment {
+    uint64_t offset; /* first coordinate of the segment */
+    uint64_t length; /* number of coordinates (0 allowed) */
+    double p;        /* probability that a coordinate of it is shuffled, in [0, 1] */
+} wash_segment;
+
+/*
+ * The shuffling step, Eq. 3 / Alg. 1: for every coordinate g of every segment,
+ * independently with probability p of its segment, draw a permutation pi_g
+ * uniform on all N! permutations (independent of the Bernoulli draw) and set
+ * params[n][g] <- params_old[pi_g(n)][g] for all n at once.  The draw is one
+ * per coordinate, shared by the N models, so each coordinate's multiset of
+ * values, the population mean and the consensus distance (Eq. 5) are kept.
+ * If `momentum` is given, the same mask and the same pi_g move it too (the
+ * WASH+Opt variant, Sec. 4).  Values are moved as raw 32-bit patterns.
+ *
+ * Randomness is a pure function of (seed, step, g, N, p): the same arguments
+ * give the same bits whatever the launch shape, however a tensor is cut into
+ * segments of equal p, and whether or not momentum is passed.  Stream "v1":
+ * Philox4x32-10 keyed by seed; mask word of g = word (g mod 4) of the call at
+ * counter (g/4, step, 0), selected iff word < round(p * 2^32); permutation
+ * words from counters (g, step, 1 + t/4); descending Fisher-Yates with
+ * multiply-high range reduction.
+ *
+ *   params          device, [N, P] fp32, updated in place
+ *   momentum        device, [N, P] fp32 or NULL; must not overlap params
+ *   N               population size, 1 .. WASH_MAX_N   (N = 1: identity)
+ *   P               coordinates per model, >= 1
+ *   segs            HOST array of nsegs segments, sorted by offset and not
+ *                   overlapping; read before the call returns.  Coordinates in
+ *                   no segment are never shuffled.
+ *   nsegs           number of segments (0 allowed: nothing happens)
+ *   seed, step      stream address; step < 2^32
+ *   selected_count  device uint64 or NULL; the number of selected coordinates
+ *                   (the per-model communication volume of Sec. 3) is ADDED to it
+ *   stream          hipStream_t
+ *
+ * Errors: WASH_EINVAL for NULL params, N = 0 or > WASH_MAX_N, P = 0, a
+ * probability outside [0, 1] or NaN, a segment outside [0, P), unsorted or
+ * overlapping segments, step >= 2^32, momentum == params; WASH_EHIP if a HIP
+ * call fails.
+ */
+int wash_shuffle(float *params, float *momentum, uint32_t N, uint64_t P,
+                 const wash_segment *segs, uint32_t nsegs,
+                 uint64_t seed, uint64_t step,
+                 uint64_t *selected_count, void *stream);
+
+/*
+ * Uniform average, Alg. 1 output line: out[g] = (1/N) sum_n params[n][g],
+ * summed in fp64 in ascending n and rounded once to fp32.
+ *   params  device, [N, P] fp32 (read only)      out  device, [P] fp32, must not overlap params
+ * Errors: WASH_EINVAL for NULL pointers, N = 0 or > WASH_MAX_N, P = 0.
+ */
+int wash_average(const float *params, float *out, uint32_t N, uint64_t P, void *stream);
+
+/*
+ * PAPA's update, Eq. 1: params[n][g] <- alpha * params[n][g] + (1 - alpha) * mean[g]
+ * for all n, where mean[g] is the average over n of the values BEFORE the
+ * update; one pass, in place, arithmetic in fp64, rounded once to fp32.
+ * alpha = 1 is the identity, alpha = 0 replaces every model by the consensus.
+ *   params  device, [N, P] fp32, in place        alpha  any finite value (the paper uses ]0,1[)
+ * Errors: WASH_EINVAL for NULL params, N = 0 or > WASH_MAX_N, P = 0, alpha NaN or infinite.
+ */
+int papa_ema(float *params, uint32_t N, uint64_t P, float alpha, void *stream);
+
+/*
+ * Layer-wise probabilities, Eq. 6 (host only): out[l] for l = 0 .. L-1.
+ *   schedule 0  decreasing, p * (1 - l/(L-1))   (Eq. 6: first layer p, last layer 0)
+ *   schedule 1  constant p
+ *   schedule 2  increasing, p * l/(L-1)         (the appendix ablation)
+ * L = 1 gives p for every schedule.  out: HOST array of L doubles.
+ * Errors: WASH_EINVAL for p outside [0,1] or NaN, L = 0, unknown schedule, NULL out.
+ */
+int wash_layer_probs(double p, uint32_t L, int schedule, double *out);
+
+/* Text for a status code (static storage, never NULL). */
+const char *wash_strerror(int status);
+
+/* Detail of the last error raised on the calling thread ("" if none). */
+const char *wash_last_error_detail(void);
+
+/*
+ * Tuning knobs (process-wide, not part of the method: results never depend
+ * on them).  Returns WASH_EINVAL for an unknown option or a value out of range.
+ *   WASH_OPT_TILE_COORDS  coordinates scanned by one wavefront in wash_shuffle;
+ *                         a multiple of 256 in [256, 65536], or 0 = choose by P
+ */
+#define WASH_OPT_TILE_COORDS 1
+int wash_set_option(int option, int64_t value);
+
+/* Free the cached device tables of every device (waits for the devices). */
+int wash_shutdown(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WASH_H */

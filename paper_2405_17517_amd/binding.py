@@ -1,0 +1,150 @@
+"""Thin ctypes binding of libwash_hip.so (declared in include/wash.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.
+torch is used for device memory and the current stream, nothing else.  If the
+library has not been built the import of this module fails loudly; there is no
+fallback implementation.
+"""
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libwash_hip.so")
+MAX_N = 32
+OPT_TILE_COORDS = 1
+
+
+class WashError(RuntimeError):
+    pass
+
+
+class Segment(ctypes.Structure):
+    _fields_ = [("offset", ctypes.c_uint64), ("length", ctypes.c_uint64), ("p", ctypes.c_double)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -m paper_2405_17517_amd.build, "
+            "or __graft_entry__.build()). There is no CPU fallback.")
+    L = ctypes.CDLL(LIB_PATH)
+    u32, u64, vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_void_p
+    L.wash_shuffle.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp, vp]
+    L.wash_shuffle.restype = ctypes.c_int
+    L.wash_average.argtypes = [vp, vp, u32, u64, vp]
+    L.wash_average.restype = ctypes.c_int
+    L.papa_ema.argtypes = [vp, u32, u64, ctypes.c_float, vp]
+    L.papa_ema.restype = ctypes.c_int
+    L.wash_layer_probs.argtypes = [ctypes.c_double, u32, ctypes.c_int, vp]
+    L.wash_layer_probs.restype = ctypes.c_int
+    L.wash_strerror.argtypes = [ctypes.c_int]
+    L.wash_strerror.restype = ctypes.c_char_p
+    L.wash_last_error_detail.argtypes = []
+    L.wash_last_error_detail.restype = ctypes.c_char_p
+    L.wash_set_option.argtypes = [ctypes.c_int, ctypes.c_int64]
+    L.wash_set_option.restype = ctypes.c_int
+    L.wash_shutdown.argtypes = []
+    L.wash_shutdown.restype = ctypes.c_int
+    return L
+
+
+_lib = _load()
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        msg = _lib.wash_strerror(rc).decode()
+        detail = _lib.wash_last_error_detail().decode()
+        raise WashError(f"{what}: {msg}" + (f" ({detail})" if detail else ""))
+
+
+def _dev_pop(t: torch.Tensor, name: str) -> Tuple[int, int]:
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32 and t.dim() == 2
+            and t.is_contiguous()):
+        raise TypeError(f"{name}: need a contiguous float32 [N, P] tensor on the GPU")
+    return t.shape[0], t.shape[1]
+
+
+def _stream(t: torch.Tensor) -> int:
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+class SegmentList:
+    """Host-side segment array, built once and reused across calls."""
+
+    def __init__(self, segs: Sequence[Tuple[int, int, float]]):
+        self.n = len(segs)
+        self.array = (Segment * max(self.n, 1))()
+        for k, (off, length, p) in enumerate(segs):
+            self.array[k].offset, self.array[k].length, self.array[k].p = int(off), int(length), float(p)
+
+    @property
+    def ptr(self) -> int:
+        return ctypes.addressof(self.array)
+
+
+def wash_shuffle(params: torch.Tensor, momentum: Optional[torch.Tensor], segs, seed: int, step: int,
+                 selected_count: Optional[torch.Tensor] = None) -> None:
+    """In-place shuffling step (Eq. 3) on a device population; see wash.h."""
+    N, P = _dev_pop(params, "params")
+    mom_ptr = None
+    if momentum is not None:
+        if _dev_pop(momentum, "momentum") != (N, P) or momentum.device != params.device:
+            raise TypeError("momentum: shape/device must match params")
+        mom_ptr = momentum.data_ptr()
+    cnt_ptr = None
+    if selected_count is not None:
+        if not (selected_count.is_cuda and selected_count.dtype == torch.int64 and selected_count.numel() == 1
+                and selected_count.device == params.device):
+            raise TypeError("selected_count: need a one-element int64 tensor on the same GPU")
+        cnt_ptr = selected_count.data_ptr()
+    if not isinstance(segs, SegmentList):
+        segs = SegmentList(segs)
+    with torch.cuda.device(params.device):
+        rc = _lib.wash_shuffle(params.data_ptr(), mom_ptr, N, P, segs.ptr, segs.n, seed, step, cnt_ptr,
+                               _stream(params))
+    _check(rc, "wash_shuffle")
+
+
+def wash_average(params: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Uniform average over the population (Alg. 1 output); returns out [P]."""
+    N, P = _dev_pop(params, "params")
+    if out is None:
+        out = torch.empty(P, dtype=torch.float32, device=params.device)
+    elif not (out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.numel() == P
+              and out.device == params.device):
+        raise TypeError("out: need a contiguous float32 [P] tensor on the same GPU")
+    with torch.cuda.device(params.device):
+        rc = _lib.wash_average(params.data_ptr(), out.data_ptr(), N, P, _stream(params))
+    _check(rc, "wash_average")
+    return out
+
+
+def papa_ema(params: torch.Tensor, alpha: float) -> None:
+    """In-place PAPA update (Eq. 1) on a device population."""
+    N, P = _dev_pop(params, "params")
+    with torch.cuda.device(params.device):
+        rc = _lib.papa_ema(params.data_ptr(), N, P, float(alpha), _stream(params))
+    _check(rc, "papa_ema")
+
+
+def wash_layer_probs(p: float, L: int, schedule: int = 0):
+    """Eq. 6 (schedule 0) and its constant / increasing variants; list of L floats."""
+    out = (ctypes.c_double * max(int(L), 1))()
+    _check(_lib.wash_layer_probs(float(p), int(L), int(schedule), ctypes.addressof(out)), "wash_layer_probs")
+    return [out[k] for k in range(L)]
+
+
+def wash_set_option(option: int, value: int) -> None:
+    _check(_lib.wash_set_option(int(option), int(value)), "wash_set_option")
+
+
+def wash_shutdown() -> None:
+    _check(_lib.wash_shutdown(), "wash_shutdown")
+
+
+# raw entry points for tests of the C ABI itself (error paths, NULL arguments)
+raw = _lib

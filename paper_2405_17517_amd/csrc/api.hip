@@ -1,0 +1,301 @@
+// C ABI of the library: argument checks, per-segment thresholds (Eq. 6 feeds
+// these through the caller), the cached device segment table, and the launches.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <list>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "../../include/wash.h"
+#include "kernels.hpp"
+
+namespace {
+
+thread_local char g_detail[256] = "";
+
+__attribute__((format(printf, 2, 3))) int fail(int status, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    std::vsnprintf(g_detail, sizeof(g_detail), fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+int fail_hip(const char *what, hipError_t e)
+{
+    std::snprintf(g_detail, sizeof(g_detail), "%s: %s", what, hipGetErrorString(e));
+    return WASH_EHIP;
+}
+
+// round(p * 2^32) as an integer in [0, 2^32]
+uint64_t threshold_of(double p)
+{
+    const double t = std::floor(p * 4294967296.0 + 0.5);
+    if (t <= 0.0) return 0;
+    if (t >= 4294967296.0) return 4294967296ull;
+    return static_cast<uint64_t>(t);
+}
+
+// ---- cached device tables: one per (device, P, tile size, active segment list) -------------
+
+struct TableKey {
+    int device;
+    uint64_t P;
+    uint32_t tile_coords;
+    std::vector<wash::DevSegment> segs;
+    bool operator==(const TableKey &o) const
+    {
+        return device == o.device && P == o.P && tile_coords == o.tile_coords && segs.size() == o.segs.size() &&
+               (segs.empty() || std::memcmp(segs.data(), o.segs.data(), segs.size() * sizeof(wash::DevSegment)) == 0);
+    }
+};
+
+struct Table {
+    TableKey key;
+    void *dev = nullptr;            // [DevSegment x nsegs][uint32 x num_tiles]
+    uint64_t num_tiles = 0;
+};
+
+std::mutex g_mutex;
+std::list<Table> g_tables;          // most recently used first
+constexpr size_t kMaxTables = 16;
+int64_t g_tile_coords_option = 0;   // 0 = choose by P
+
+uint32_t choose_tile_coords(uint64_t P)
+{
+    if (g_tile_coords_option != 0) return static_cast<uint32_t>(g_tile_coords_option);
+    // enough tiles to give each of the 1024 SIMDs several wavefronts, at most 4096 coordinates each
+    uint32_t t = 4096;
+    while (t > 256 && (P + t - 1) / t < 8192) t >>= 1;
+    return t;
+}
+
+// Builds (or finds) the device table for this call; on success *out points at the cached entry.
+int get_table(int device, uint64_t P, uint32_t tile_coords, std::vector<wash::DevSegment> &&active,
+              const Table **out)
+{
+    TableKey key{device, P, tile_coords, std::move(active)};
+    for (auto it = g_tables.begin(); it != g_tables.end(); ++it) {
+        if (it->key == key) {
+            g_tables.splice(g_tables.begin(), g_tables, it);
+            *out = &g_tables.front();
+            return WASH_OK;
+        }
+    }
+    const uint64_t num_tiles = (P + tile_coords - 1) / tile_coords;
+    const size_t nsegs = key.segs.size();
+    const size_t seg_bytes = nsegs * sizeof(wash::DevSegment);
+    const size_t bytes = seg_bytes + num_tiles * sizeof(uint32_t);
+    std::vector<unsigned char> host;
+    try {
+        host.resize(bytes);
+    } catch (const std::bad_alloc &) {
+        return fail(WASH_ENOMEM, "segment table of %zu bytes", bytes);
+    }
+    std::memcpy(host.data(), key.segs.data(), seg_bytes);
+    uint32_t *tile_first = reinterpret_cast<uint32_t *>(host.data() + seg_bytes);
+    size_t s = 0;
+    for (uint64_t t = 0; t < num_tiles; ++t) {
+        const uint64_t begin = t * tile_coords;
+        const uint64_t end = (begin + tile_coords < P) ? begin + tile_coords : P;
+        while (s < nsegs && key.segs[s].end <= begin) ++s;
+        tile_first[t] = (s < nsegs && key.segs[s].begin < end) ? static_cast<uint32_t>(s) : wash::kNoSegment;
+    }
+    if (g_tables.size() >= kMaxTables) {
+        // hipFree waits for the device, so no launched kernel still reads the table
+        (void)hipSetDevice(g_tables.back().key.device);
+        (void)hipFree(g_tables.back().dev);
+        (void)hipSetDevice(device);
+        g_tables.pop_back();
+    }
+    void *dev = nullptr;
+    hipError_t e = hipMalloc(&dev, bytes);
+    if (e != hipSuccess) return fail_hip("hipMalloc(segment table)", e);
+    e = hipMemcpy(dev, host.data(), bytes, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(dev);
+        return fail_hip("hipMemcpy(segment table)", e);
+    }
+    g_tables.emplace_front();
+    g_tables.front().key = std::move(key);
+    g_tables.front().dev = dev;
+    g_tables.front().num_tiles = num_tiles;
+    *out = &g_tables.front();
+    return WASH_OK;
+}
+
+bool ranges_overlap(const void *a, uint64_t abytes, const void *b, uint64_t bbytes)
+{
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+    return x < y + bbytes && y < x + abytes;
+}
+
+int check_population(const void *params, uint32_t N, uint64_t P)
+{
+    if (params == nullptr) return fail(WASH_EINVAL, "params is NULL");
+    if (N == 0 || N > WASH_MAX_N) return fail(WASH_EINVAL, "N must be in 1..32, got %u", N);
+    if (P == 0) return fail(WASH_EINVAL, "P must be >= 1");
+    if (P > (1ull << 40)) return fail(WASH_EINVAL, "P larger than 2^40 is not supported");
+    return WASH_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int wash_shuffle(float *params, float *momentum, uint32_t N, uint64_t P, const wash_segment *segs,
+                 uint32_t nsegs, uint64_t seed, uint64_t step, uint64_t *selected_count, void *stream)
+{
+    g_detail[0] = 0;
+    if (int rc = check_population(params, N, P)) return rc;
+    if (step >= (1ull << 32)) return fail(WASH_EINVAL, "step must be < 2^32");
+    if (nsegs > 0 && segs == nullptr) return fail(WASH_EINVAL, "segs is NULL");
+    const uint64_t pop_bytes = static_cast<uint64_t>(N) * P * sizeof(float);
+    if (momentum != nullptr && ranges_overlap(params, pop_bytes, momentum, pop_bytes))
+        return fail(WASH_EINVAL, "momentum overlaps params");
+
+    std::vector<wash::DevSegment> active;
+    try {
+        active.reserve(nsegs);
+    } catch (const std::bad_alloc &) {
+        return fail(WASH_ENOMEM, "segment list");
+    }
+    uint64_t prev_end = 0;
+    for (uint32_t s = 0; s < nsegs; ++s) {
+        const wash_segment &sg = segs[s];
+        if (!(sg.p >= 0.0 && sg.p <= 1.0))
+            return fail(WASH_EINVAL, "segment %u: probability outside [0,1]", s);
+        if (sg.offset > P || sg.length > P - sg.offset)
+            return fail(WASH_EINVAL, "segment %u: outside [0,P)", s);
+        if (sg.offset < prev_end)
+            return fail(WASH_EINVAL, "segment %u: unsorted or overlapping", s);
+        prev_end = sg.offset + sg.length;
+        const uint64_t T = threshold_of(sg.p);
+        if (T == 0 || sg.length == 0) continue;     // never selected: not scanned at all
+        wash::DevSegment d{sg.offset, sg.offset + sg.length, static_cast<uint32_t>(T - 1u), 0u};
+        // neighbours with the same threshold behave as one segment
+        if (!active.empty() && active.back().end == d.begin && active.back().thr_m1 == d.thr_m1)
+            active.back().end = d.end;
+        else
+            active.push_back(d);
+    }
+    if (active.empty()) return WASH_OK;
+
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return fail_hip("hipGetDevice", e);
+
+    std::lock_guard<std::mutex> lock(g_mutex);
+    const uint32_t tile_coords = choose_tile_coords(P);
+    const Table *table = nullptr;
+    if (int rc = get_table(device, P, tile_coords, std::move(active), &table)) return rc;
+
+    wash::ShuffleArgs a{};
+    a.params = reinterpret_cast<uint32_t *>(params);
+    a.momentum = reinterpret_cast<uint32_t *>(momentum);
+    a.N = N;
+    a.P = P;
+    a.segs = static_cast<const wash::DevSegment *>(table->dev);
+    a.nsegs = static_cast<uint32_t>(table->key.segs.size());
+    a.tile_first = reinterpret_cast<const uint32_t *>(static_cast<const unsigned char *>(table->dev) +
+                                                      table->key.segs.size() * sizeof(wash::DevSegment));
+    a.num_tiles = table->num_tiles;
+    a.tile_coords = tile_coords;
+    a.key_lo = static_cast<uint32_t>(seed);
+    a.key_hi = static_cast<uint32_t>(seed >> 32);
+    a.step = static_cast<uint32_t>(step);
+    a.selected_count = reinterpret_cast<unsigned long long *>(selected_count);
+    e = wash::launch_shuffle(a, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip("wash_shuffle launch", e);
+    return WASH_OK;
+}
+
+int wash_average(const float *params, float *out, uint32_t N, uint64_t P, void *stream)
+{
+    g_detail[0] = 0;
+    if (int rc = check_population(params, N, P)) return rc;
+    if (out == nullptr) return fail(WASH_EINVAL, "out is NULL");
+    if (ranges_overlap(params, static_cast<uint64_t>(N) * P * sizeof(float), out, P * sizeof(float)))
+        return fail(WASH_EINVAL, "out overlaps params");
+    const hipError_t e = wash::launch_average(params, out, N, P, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip("wash_average launch", e);
+    return WASH_OK;
+}
+
+int papa_ema(float *params, uint32_t N, uint64_t P, float alpha, void *stream)
+{
+    g_detail[0] = 0;
+    if (int rc = check_population(params, N, P)) return rc;
+    if (!std::isfinite(alpha)) return fail(WASH_EINVAL, "alpha is not finite");
+    const hipError_t e = wash::launch_ema(params, N, P, alpha, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip("papa_ema launch", e);
+    return WASH_OK;
+}
+
+int wash_layer_probs(double p, uint32_t L, int schedule, double *out)
+{
+    g_detail[0] = 0;
+    if (!(p >= 0.0 && p <= 1.0)) return fail(WASH_EINVAL, "p outside [0,1]");
+    if (L == 0) return fail(WASH_EINVAL, "L must be >= 1");
+    if (out == nullptr) return fail(WASH_EINVAL, "out is NULL");
+    if (schedule < 0 || schedule > 2) return fail(WASH_EINVAL, "unknown schedule %d", schedule);
+    for (uint32_t l = 0; l < L; ++l) {
+        // depth fraction l/(L-1); a single layer keeps the base probability
+        const double depth = (L > 1) ? static_cast<double>(l) / static_cast<double>(L - 1) : 0.0;
+        switch (schedule) {
+        case 0: out[l] = p * (1.0 - depth); break;
+        case 1: out[l] = p; break;
+        default: out[l] = (L > 1) ? p * depth : p; break;
+        }
+    }
+    return WASH_OK;
+}
+
+const char *wash_strerror(int status)
+{
+    switch (status) {
+    case WASH_OK: return "success";
+    case WASH_EINVAL: return "invalid argument";
+    case WASH_EHIP: return "HIP call failed";
+    case WASH_ENOMEM: return "out of host memory";
+    default: return "unknown status";
+    }
+}
+
+const char *wash_last_error_detail(void) { return g_detail; }
+
+int wash_set_option(int option, int64_t value)
+{
+    g_detail[0] = 0;
+    if (option == WASH_OPT_TILE_COORDS) {
+        if (value != 0 && (value < 256 || value > 65536 || value % 256 != 0))
+            return fail(WASH_EINVAL, "tile coordinates must be 0 or a multiple of 256 in [256, 65536]");
+        std::lock_guard<std::mutex> lock(g_mutex);
+        g_tile_coords_option = value;
+        return WASH_OK;
+    }
+    return fail(WASH_EINVAL, "unknown option %d", option);
+}
+
+int wash_shutdown(void)
+{
+    g_detail[0] = 0;
+    std::lock_guard<std::mutex> lock(g_mutex);
+    int rc = WASH_OK;
+    int current = 0;
+    const bool have_current = hipGetDevice(&current) == hipSuccess;
+    for (Table &t : g_tables) {
+        if (hipSetDevice(t.key.device) != hipSuccess || hipFree(t.dev) != hipSuccess) rc = WASH_EHIP;
+    }
+    g_tables.clear();
+    if (have_current) (void)hipSetDevice(current);
+    return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,37 @@
+// Internal launchers behind the C ABI (host side; all pointers are device memory).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace wash {
+
+// One active segment (probability > 0, length > 0) as the shuffle kernel sees it.
+struct DevSegment {
+    uint64_t begin;     // first coordinate
+    uint64_t end;       // one past the last coordinate
+    uint32_t thr_m1;    // coordinate selected  <=>  mask word <= thr_m1   (= round(p*2^32) - 1)
+    uint32_t pad;
+};
+
+constexpr uint32_t kNoSegment = 0xFFFFFFFFu;
+
+struct ShuffleArgs {
+    uint32_t *params;           // [N, P] as raw 32-bit words
+    uint32_t *momentum;         // [N, P] or nullptr
+    uint32_t N;
+    uint64_t P;
+    const DevSegment *segs;     // nsegs active segments, ascending
+    uint32_t nsegs;
+    const uint32_t *tile_first; // per tile: first active segment ending after the tile start, or kNoSegment
+    uint64_t num_tiles;
+    uint32_t tile_coords;       // coordinates per tile (one wavefront scans one tile), multiple of 256
+    uint32_t key_lo, key_hi;    // seed
+    uint32_t step;
+    unsigned long long *selected_count; // or nullptr
+};
+
+hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream);
+hipError_t launch_average(const float *params, float *out, uint32_t N, uint64_t P, hipStream_t stream);
+hipError_t launch_ema(float *params, uint32_t N, uint64_t P, float alpha, hipStream_t stream);
+
+}  // namespace wash

@@ -1,0 +1,159 @@
+// wash_average (Alg. 1 output line) and papa_ema (Sec. 3, Eq. 1) for gfx950.
+//
+// Both are pure streaming passes bound by HBM bandwidth: every thread owns 4
+// consecutive coordinates, issues the N independent 16-byte loads of its column
+// block before using any of them, accumulates in fp64 in ascending n (the same
+// order and precision as the plain definition, so the fp32 result is the
+// correctly rounded one) and writes 16 bytes per row.  N is a template
+// parameter so the N values stay in registers: the EMA reads and writes each
+// element exactly once.  Rows are P elements apart and P need not be a multiple
+// of 4, so the 16-byte accesses are only 4-byte aligned; gfx950 global memory
+// accepts that.
+#include "kernels.hpp"
+
+namespace wash {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+
+// fp64 arithmetic is kept unfused so that it matches the definition operation by operation
+#pragma clang fp contract(off)
+
+template <int N>
+__global__ __launch_bounds__(kThreads) void average_kernel(const float *__restrict__ params,
+                                                           float *__restrict__ out, uint64_t P)
+{
+    const uint64_t base = (static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4u;
+    if (base >= P) return;
+    const double inv_den = static_cast<double>(N);
+    if (base + 4u <= P) {
+        f4u v[N];
+#pragma unroll
+        for (int n = 0; n < N; ++n)
+            v[n] = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(params + static_cast<uint64_t>(n) * P + base));
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            s0 += static_cast<double>(v[n].x);
+            s1 += static_cast<double>(v[n].y);
+            s2 += static_cast<double>(v[n].z);
+            s3 += static_cast<double>(v[n].w);
+        }
+        f4u o;
+        o.x = static_cast<float>(s0 / inv_den);
+        o.y = static_cast<float>(s1 / inv_den);
+        o.z = static_cast<float>(s2 / inv_den);
+        o.w = static_cast<float>(s3 / inv_den);
+        __builtin_nontemporal_store(o, reinterpret_cast<f4u *>(out + base));
+    } else {
+        for (uint64_t g = base; g < P; ++g) {
+            double s = 0.0;
+#pragma unroll
+            for (int n = 0; n < N; ++n) s += static_cast<double>(params[static_cast<uint64_t>(n) * P + g]);
+            out[g] = static_cast<float>(s / inv_den);
+        }
+    }
+}
+
+template <int N>
+__global__ __launch_bounds__(kThreads) void ema_kernel(float *__restrict__ params, uint64_t P, double alpha)
+{
+    const uint64_t base = (static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4u;
+    if (base >= P) return;
+    const double den = static_cast<double>(N);
+    const double beta = 1.0 - alpha;
+    if (base + 4u <= P) {
+        f4u v[N];
+#pragma unroll
+        for (int n = 0; n < N; ++n)
+            v[n] = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(params + static_cast<uint64_t>(n) * P + base));
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            s0 += static_cast<double>(v[n].x);
+            s1 += static_cast<double>(v[n].y);
+            s2 += static_cast<double>(v[n].z);
+            s3 += static_cast<double>(v[n].w);
+        }
+        const double m0 = beta * (s0 / den), m1 = beta * (s1 / den), m2 = beta * (s2 / den), m3 = beta * (s3 / den);
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            f4u o;
+            o.x = static_cast<float>(alpha * static_cast<double>(v[n].x) + m0);
+            o.y = static_cast<float>(alpha * static_cast<double>(v[n].y) + m1);
+            o.z = static_cast<float>(alpha * static_cast<double>(v[n].z) + m2);
+            o.w = static_cast<float>(alpha * static_cast<double>(v[n].w) + m3);
+            __builtin_nontemporal_store(o, reinterpret_cast<f4u *>(params + static_cast<uint64_t>(n) * P + base));
+        }
+    } else {
+        for (uint64_t g = base; g < P; ++g) {
+            double s = 0.0;
+#pragma unroll
+            for (int n = 0; n < N; ++n) s += static_cast<double>(params[static_cast<uint64_t>(n) * P + g]);
+            const double m = beta * (s / den);
+#pragma unroll
+            for (int n = 0; n < N; ++n) {
+                float *q = params + static_cast<uint64_t>(n) * P + g;
+                *q = static_cast<float>(alpha * static_cast<double>(*q) + m);
+            }
+        }
+    }
+}
+
+inline bool grid_for(uint64_t P, dim3 &grid)
+{
+    const uint64_t threads = (P + 3u) / 4u;
+    const uint64_t blocks = (threads + kThreads - 1) / kThreads;
+    if (blocks == 0 || blocks > 0x7FFFFFFFull) return false;
+    grid = dim3(static_cast<uint32_t>(blocks));
+    return true;
+}
+
+template <int N>
+hipError_t run_average(const float *params, float *out, uint64_t P, hipStream_t stream)
+{
+    dim3 grid;
+    if (!grid_for(P, grid)) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(average_kernel<N>, grid, dim3(kThreads), 0, stream, params, out, P);
+    return hipGetLastError();
+}
+
+template <int N>
+hipError_t run_ema(float *params, uint64_t P, double alpha, hipStream_t stream)
+{
+    dim3 grid;
+    if (!grid_for(P, grid)) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(ema_kernel<N>, grid, dim3(kThreads), 0, stream, params, P, alpha);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+#define WASH_FOR_EACH_N(X)                                                                         \
+    X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17)   \
+    X(18) X(19) X(20) X(21) X(22) X(23) X(24) X(25) X(26) X(27) X(28) X(29) X(30) X(31) X(32)
+
+hipError_t launch_average(const float *params, float *out, uint32_t N, uint64_t P, hipStream_t stream)
+{
+    switch (N) {
+#define X(n) case n: return run_average<n>(params, out, P, stream);
+        WASH_FOR_EACH_N(X)
+#undef X
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_ema(float *params, uint32_t N, uint64_t P, float alpha, hipStream_t stream)
+{
+    switch (N) {
+#define X(n) case n: return run_ema<n>(params, P, static_cast<double>(alpha), stream);
+        WASH_FOR_EACH_N(X)
+#undef X
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace wash

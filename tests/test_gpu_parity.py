@@ -1,0 +1,181 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.  Shuffle: bit-exact.  Average / EMA: 1e-6 relative (the
+kernels accumulate in fp64 like the definition, so they are normally identical)."""
+import numpy as np
+import pytest
+
+import oracle
+from workloads import distinct_population
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def wash():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2405_17517_amd as w
+    yield w
+    w.wash_set_option(w.OPT_TILE_COORDS, 0)
+
+
+def _bits(a):
+    return a.view(np.uint32)
+
+
+def _ragged_segments(P, ps):
+    """Cut [0, P) into len(ps) pieces at odd places, leaving a gap before the last piece."""
+    k = len(ps)
+    edges = sorted({0, P} | {max(1, min(P - 1, (P * i) // k + (3 * i) % 7 - 3)) for i in range(1, k)})
+    segs = []
+    for i in range(len(edges) - 1):
+        a, b = edges[i], edges[i + 1]
+        if i == len(edges) - 2 and b - a > 4:
+            a += 3                                   # uncovered gap
+        segs.append((a, b - a, ps[i % k]))
+    return segs
+
+
+def _run_shuffle(wash, pop, mom, segs, seed, step, tile=0):
+    wash.wash_set_option(wash.OPT_TILE_COORDS, tile)
+    d = torch.from_numpy(pop).cuda()
+    dm = torch.from_numpy(mom).cuda() if mom is not None else None
+    cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+    wash.wash_shuffle(d, dm, segs, seed, step, cnt)
+    torch.cuda.synchronize()
+    return d.cpu().numpy(), (dm.cpu().numpy() if dm is not None else None), int(cnt.item())
+
+
+SHAPES = [(1, 1), (1, 77), (2, 3), (2, 255), (3, 256), (4, 257), (5, 4097), (8, 12289), (10, 70001),
+          (20, 33333), (31, 5000), (32, 20011)]
+
+
+@pytest.mark.parametrize("N,P", SHAPES)
+@pytest.mark.parametrize("p", [0.0, 0.001, 0.05, 0.5, 1.0])
+def test_shuffle_one_segment(wash, N, P, p):
+    print(f"case N={N} P={P} p={p}", flush=True)
+    pop = distinct_population(N, P)
+    segs = [(0, P, p)]
+    ref = pop.copy()
+    ref_cnt = oracle.shuffle(ref, None, segs, 17, 4)
+    got, _, cnt = _run_shuffle(wash, pop, None, segs, 17, 4)
+    assert cnt == ref_cnt
+    assert np.array_equal(_bits(got), _bits(ref))
+
+
+@pytest.mark.parametrize("N,P", [(2, 1000), (5, 40001), (10, 123457), (20, 65539), (32, 9001)])
+@pytest.mark.parametrize("tile", [0, 256, 4096, 65536])
+def test_shuffle_ragged_segments_momentum(wash, N, P, tile):
+    print(f"case N={N} P={P} tile={tile}", flush=True)
+    pop = distinct_population(N, P)
+    mom = distinct_population(N, P, base=0x40000000)
+    segs = _ragged_segments(P, [0.3, 0.0, 1.0, 0.01, 0.3, 0.3, 0.002, 0.9, 0.05])
+    ref, refm = pop.copy(), mom.copy()
+    ref_cnt = oracle.shuffle(ref, refm, segs, 0xABCDEF0123456789, 4294967295)
+    got, gotm, cnt = _run_shuffle(wash, pop, mom, segs, 0xABCDEF0123456789, 4294967295, tile)
+    assert cnt == ref_cnt
+    assert np.array_equal(_bits(got), _bits(ref))
+    assert np.array_equal(_bits(gotm), _bits(refm))
+
+
+def test_shuffle_many_tiny_segments(wash):
+    # tensors of 1..70 elements back to back, probabilities cycling, some zero
+    N, P = 6, 50000
+    rng = np.random.default_rng(0)
+    segs, off, k = [], 0, 0
+    while off < P - 100:
+        ln = int(rng.integers(1, 70))
+        segs.append((off, ln, [0.5, 0.0, 1.0, 0.1, 0.5][k % 5]))
+        off += ln + (1 if k % 11 == 0 else 0)
+        k += 1
+    pop = distinct_population(N, P)
+    ref = pop.copy()
+    ref_cnt = oracle.shuffle(ref, None, segs, 5, 6)
+    for tile in (256, 1024, 0):
+        got, _, cnt = _run_shuffle(wash, pop, None, segs, 5, 6, tile)
+        assert cnt == ref_cnt and np.array_equal(_bits(got), _bits(ref))
+
+
+def test_shuffle_consecutive_steps_and_special_values(wash):
+    N, P = 7, 30011
+    bits = np.random.default_rng(1).integers(0, 2 ** 32, size=(N, P), dtype=np.uint64).astype(np.uint32)
+    bits[:, :3] = np.array([0x7FC00001, 0xFFC12345, 0x80000000], dtype=np.uint32)   # NaN payloads, -0.0
+    pop = bits.view(np.float32).copy()
+    segs = [(0, P, 0.2)]
+    ref = pop.copy()
+    d = torch.from_numpy(pop).cuda()
+    for step in range(12):
+        oracle.shuffle(ref, None, segs, 3, step)
+        wash.wash_shuffle(d, None, segs, 3, step)
+    torch.cuda.synchronize()
+    assert np.array_equal(_bits(d.cpu().numpy()), _bits(ref))
+
+
+def test_shuffle_is_deterministic_and_tile_independent(wash):
+    N, P = 10, 1 << 18
+    pop = distinct_population(N, P)
+    segs = [(0, P, 0.03)]
+    outs = [_run_shuffle(wash, pop, None, segs, 1, 2, tile)[0] for tile in (0, 256, 512, 8192, 0)]
+    for o in outs[1:]:
+        assert np.array_equal(_bits(o), _bits(outs[0]))
+
+
+@pytest.mark.parametrize("N,P", [(1, 5), (2, 1023), (4, 1 << 20), (5, 1000003), (10, 300001), (20, 70002), (32, 4099)])
+def test_average_and_ema(wash, N, P):
+    print(f"case N={N} P={P}", flush=True)
+    rng = np.random.default_rng(N * 1000 + P % 1000)
+    pop = (rng.standard_normal((N, P)) * 0.02).astype(np.float32)
+    d = torch.from_numpy(pop).cuda()
+    avg = wash.wash_average(d).cpu().numpy()
+    ref = oracle.average(pop)
+    scale = np.maximum(np.abs(ref), np.abs(pop).mean(axis=0))
+    assert np.all(np.abs(avg - ref) <= 1e-6 * scale)
+    assert np.array_equal(avg, ref)          # fp64 accumulation in the same order: identical
+    for alpha in (0.99, 0.0, 1.0, 0.37):
+        d = torch.from_numpy(pop).cuda()
+        wash.papa_ema(d, alpha)
+        got = d.cpu().numpy()
+        e = pop.copy()
+        oracle.ema(e, alpha)
+        scale = np.maximum(np.abs(e), np.abs(pop).mean(axis=0, keepdims=True))
+        assert np.all(np.abs(got - e) <= 1e-6 * scale)
+        assert np.array_equal(got, e)
+
+
+def test_shuffle_keeps_mean_and_multiset_on_device(wash):
+    N, P = 5, 2_000_003
+    rng = np.random.default_rng(9)
+    pop = (rng.standard_normal((N, P)) * 0.02).astype(np.float32)
+    d = torch.from_numpy(pop).cuda()
+    before = wash.wash_average(d).clone()
+    xor0 = torch.sort(d.view(torch.int32), dim=0).values.clone()
+    wash.wash_shuffle(d, None, [(0, P, 0.1)], 8, 0)
+    assert torch.equal(torch.sort(d.view(torch.int32), dim=0).values, xor0)
+    assert not torch.equal(d.cpu(), torch.from_numpy(pop))
+    after = wash.wash_average(d)
+    # the sum is taken in ascending n, so a permuted column may round differently in fp64;
+    # after rounding to fp32 that is below the 1e-6 bar by orders of magnitude
+    assert torch.allclose(after, before, rtol=1e-6, atol=1e-9)
+
+
+def test_error_paths_launch_nothing(wash):
+    d = torch.zeros((2, 100), dtype=torch.float32, device="cuda")
+    d.copy_(torch.arange(200, dtype=torch.float32, device="cuda").view(2, 100))
+    keep = d.clone()
+    for segs in ([(0, 101, 0.5)], [(50, 60, 0.5)], [(0, 10, 1.5)], [(0, 10, float("nan"))],
+                 [(10, 10, 0.5), (0, 5, 0.5)], [(0, 10, 0.5), (9, 5, 0.5)]):
+        with pytest.raises(wash.WashError):
+            wash.wash_shuffle(d, None, segs, 0, 0)
+    with pytest.raises(wash.WashError):
+        wash.wash_shuffle(d, None, [(0, 100, 0.5)], 0, 1 << 32)
+    with pytest.raises(wash.WashError):
+        wash.wash_shuffle(d, d, [(0, 100, 0.5)], 0, 0)
+    with pytest.raises(wash.WashError):
+        wash.papa_ema(d, float("nan"))
+    big = torch.zeros((33, 4), dtype=torch.float32, device="cuda")
+    with pytest.raises(wash.WashError):
+        wash.wash_average(big)
+    torch.cuda.synchronize()
+    assert torch.equal(d, keep)

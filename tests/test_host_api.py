@@ -1,0 +1,88 @@
+"""CPU-only checks of the product's host side: the library loads, exports every
+symbol the header declares, and its host-only entry points behave (no compute
+call is made here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2405_17517_amd", "libwash_hip.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        pytest.fail("libwash_hip.so is not built: run __graft_entry__.build() first")
+    return ctypes.CDLL(LIB)
+
+
+def _declared_functions():
+    src = open(os.path.join(ROOT, "include", "wash.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(wash_[a-z_]+|papa_ema)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert {"wash_shuffle", "wash_average", "papa_ema", "wash_layer_probs", "wash_strerror"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_layer_probs_match_oracle(lib):
+    lib.wash_layer_probs.argtypes = [ctypes.c_double, ctypes.c_uint32, ctypes.c_int, ctypes.c_void_p]
+    for p, L in [(0.001, 62), (0.05, 161), (1.0, 2), (0.3, 1), (0.0, 7)]:
+        for sched in (0, 1, 2):
+            out = (ctypes.c_double * L)()
+            assert lib.wash_layer_probs(p, L, sched, ctypes.addressof(out)) == 0
+            assert list(out) == list(oracle.layer_probs(p, L, sched))
+    out = (ctypes.c_double * 4)()
+    for bad in ((-0.5, 4, 0), (float("nan"), 4, 0), (0.5, 0, 0), (0.5, 4, 9)):
+        assert lib.wash_layer_probs(*bad, ctypes.addressof(out)) == -1
+    assert lib.wash_layer_probs(0.5, 4, 0, None) == -1
+
+
+def test_strerror_and_options(lib):
+    lib.wash_strerror.restype = ctypes.c_char_p
+    lib.wash_last_error_detail.restype = ctypes.c_char_p
+    lib.wash_set_option.argtypes = [ctypes.c_int, ctypes.c_int64]
+    assert lib.wash_strerror(0) == b"success"
+    assert lib.wash_strerror(-1) == b"invalid argument"
+    assert lib.wash_strerror(-77) == b"unknown status"
+    assert lib.wash_set_option(1, 512) == 0 and lib.wash_set_option(1, 0) == 0
+    assert lib.wash_set_option(1, 100) == -1 and b"256" in lib.wash_last_error_detail()
+    assert lib.wash_set_option(99, 0) == -1
+
+
+def test_validation_happens_before_any_gpu_call(lib):
+    # invalid arguments are rejected on the host, so these return without touching a device
+    u32, u64, vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_void_p
+    lib.wash_shuffle.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp, vp]
+    lib.wash_average.argtypes = [vp, vp, u32, u64, vp]
+    lib.papa_ema.argtypes = [vp, u32, u64, ctypes.c_float, vp]
+    assert lib.wash_shuffle(None, None, 2, 10, None, 0, 0, 0, None, None) == -1
+    assert lib.wash_shuffle(4096, None, 0, 10, None, 0, 0, 0, None, None) == -1
+    assert lib.wash_shuffle(4096, None, 33, 10, None, 0, 0, 0, None, None) == -1
+    assert lib.wash_shuffle(4096, None, 2, 0, None, 0, 0, 0, None, None) == -1
+    assert lib.wash_shuffle(4096, None, 2, 10, None, 1, 0, 0, None, None) == -1
+    assert lib.wash_shuffle(4096, None, 2, 10, None, 0, 0, 0, None, None) == 0      # no segments: nothing to do
+    assert lib.wash_average(None, 4096, 2, 10, None) == -1
+    assert lib.wash_average(4096, None, 2, 10, None) == -1
+    assert lib.wash_average(4096, 4100, 2, 10, None) == -1                          # out overlaps params
+    assert lib.papa_ema(None, 2, 10, 0.5, None) == -1
+    assert lib.papa_ema(4096, 2, 10, float("inf"), None) == -1
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    import paper_2405_17517_amd as w
+    with pytest.raises(TypeError):
+        w.wash_shuffle(torch.zeros(2, 8), None, [(0, 8, 0.5)], 0, 0)
+    with pytest.raises(TypeError):
+        w.wash_average(torch.zeros(2, 8))
+    with pytest.raises(TypeError):
+        w.papa_ema(torch.zeros(2, 8), 0.5)
