@@ -1,0 +1,292 @@
+#!/usr/bin/env python3
+"""Benchmark of the WASH population-update hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C] [--all-configs]
+
+A "step" is one pass of the whole hot path over the population of the chosen
+workload: one wash_shuffle (thresholds, mask, permutation, gather-permute-
+scatter, plus momentum where the workload has it), one papa_ema (on its own
+copy of the population) and one wash_average.  Inputs are resident in HBM
+before the timed region; timing uses HIP events on the stream the kernels are
+launched on.  One JSON line is printed (see the design doc for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+
+def _median(xs):
+    s = sorted(xs)
+    return s[len(s) // 2]
+
+
+def _expected_fraction(segs, P):
+    return sum(length * p for _, length, p in segs) / P
+
+
+class Timer:
+    """HIP events on the current stream; elapsed() in ms after a synchronize."""
+
+    def __init__(self, torch):
+        self.torch = torch
+        self.pairs = {}
+
+    def record(self, key, fn):
+        a = self.torch.cuda.Event(enable_timing=True)
+        b = self.torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        self.pairs.setdefault(key, []).append((a, b))
+
+    def ms(self, key):
+        return [a.elapsed_time(b) for a, b in self.pairs.get(key, [])]
+
+
+def kernel_rooflines(N, P, bufs, frac_selected, t_ms):
+    """Algorithmic bytes per launch and achieved GB/s per kernel.
+    shuffle: 2 * p * N * P * 4 B per buffer; average: (N + 1) * P * 4 B; EMA: 2 * N * P * 4 B."""
+    alg = {
+        "wash_shuffle": 2.0 * frac_selected * N * P * 4.0 * bufs,
+        "wash_average": (N + 1.0) * P * 4.0,
+        "papa_ema": 2.0 * N * P * 4.0,
+    }
+    out = {}
+    for k, b in alg.items():
+        if k in t_ms and t_ms[k] > 0:
+            gbs = b / (t_ms[k] * 1e-3) / 1e9
+            out[k] = {"bound": "hbm", "alg_bytes": b, "avg_us": t_ms[k] * 1e3, "achieved": gbs,
+                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
+    return out
+
+
+def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True):
+    """Time the hot path on one workload. Returns a dict of measurements."""
+    from workloads import device_population
+
+    dev = "cuda:0"
+    tensors = cfg.tensors()
+    N, P = cfg.N, cfg.P
+    segs_list = cfg.segments(p_override)
+    segs = wash.SegmentList(segs_list)
+    pop, mom = device_population(tensors, N, cfg.init, cfg.data_seed, cfg.momentum, dev)
+    bufs = 2 if cfg.momentum else 1
+    big = N * P * 4 > 8 * (1 << 30)
+    ema_buf = pop if big else pop.clone()      # EMA works on its own copy unless the population is huge
+    out = torch.empty(P, dtype=torch.float32, device=dev)
+    cnt = torch.zeros(1, dtype=torch.int64, device=dev)
+    torch.cuda.synchronize()
+
+    step_no = [0]
+
+    def do_shuffle():
+        wash.wash_shuffle(pop, mom, segs, cfg.seed, step_no[0], cnt if count else None)
+        step_no[0] += 1
+
+    def do_ema():
+        wash.papa_ema(ema_buf, cfg.alpha)
+
+    def do_avg():
+        wash.wash_average(pop, out)
+
+    for _ in range(warmup):
+        do_shuffle()
+        do_ema()
+        do_avg()
+    torch.cuda.synchronize()
+    cnt.zero_()
+    torch.cuda.synchronize()
+
+    tm = Timer(torch)
+    t0 = torch.cuda.Event(enable_timing=True)
+    t1 = torch.cuda.Event(enable_timing=True)
+    wall0 = time.perf_counter()
+    t0.record()
+    for _ in range(steps):
+        tm.record("wash_shuffle", do_shuffle)
+        tm.record("papa_ema", do_ema)
+        tm.record("wash_average", do_avg)
+    t1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    total_ms = t0.elapsed_time(t1)
+
+    avg_ms = {k: sum(tm.ms(k)) / steps for k in ("wash_shuffle", "papa_ema", "wash_average")}
+    med_ms = {k: _median(tm.ms(k)) for k in avg_ms}
+    selected = int(cnt.item()) / steps
+    frac_sel = _expected_fraction(segs_list, P)
+    res = {
+        "config": cfg.index, "name": cfg.name, "N": N, "P": P, "segments": len(segs_list),
+        "momentum": bool(cfg.momentum), "expected_fraction": frac_sel,
+        "selected_per_step": selected, "steps": steps,
+        "ms_per_step": total_ms / steps, "wall_ms_per_step": wall * 1e3 / steps,
+        "avg_us": {k: v * 1e3 for k, v in avg_ms.items()},
+        "median_us": {k: v * 1e3 for k, v in med_ms.items()},
+        "shuffle_coords_per_s": P / (avg_ms["wash_shuffle"] * 1e-3),
+        "pass_coords_per_s": P / (total_ms / steps * 1e-3),
+        "population_bytes": N * P * 4 * bufs,
+        "cache_resident": N * P * 4 * bufs <= 256 * (1 << 20),
+        "roofline": kernel_rooflines(N, P, bufs, frac_sel, avg_ms),
+    }
+    del pop, mom, ema_buf, out
+    torch.cuda.empty_cache()
+    return res
+
+
+def copy_yardstick(torch, wash, n_floats=1 << 28, reps=10):
+    src = torch.empty(n_floats, dtype=torch.float32, device="cuda:0").normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        wash.wash_copy_f32(src, dst)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        wash.wash_copy_f32(src, dst)
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / reps
+    gbs = 2.0 * n_floats * 4 / (ms * 1e-3) / 1e9
+    return {"bytes": 2 * n_floats * 4, "avg_us": ms * 1e3, "GBps": gbs, "frac_of_peak": gbs / HBM_PEAK_GBS}
+
+
+def cpu_baseline(cfg, budget_s=20.0):
+    """The oracle as it stands, single thread, on the same workload: whole passes
+    (shuffle + EMA + average) until about budget_s seconds of CPU work are spent."""
+    import oracle
+    from workloads import host_population
+
+    pop, mom = host_population(cfg.tensors(), cfg.N, cfg.init, cfg.data_seed, cfg.momentum)
+    segs = cfg.segments()
+    ema_buf = pop.copy()
+    passes, t_spent = 0, 0.0
+    parts = {"wash_shuffle": 0.0, "papa_ema": 0.0, "wash_average": 0.0}
+    while passes < 1 or (t_spent < budget_s and passes < 50):
+        t0 = time.perf_counter()
+        oracle.shuffle(pop, mom, segs, cfg.seed, passes, threads=1)
+        t1 = time.perf_counter()
+        oracle.ema(ema_buf, cfg.alpha)
+        t2 = time.perf_counter()
+        oracle.average(pop)
+        t3 = time.perf_counter()
+        parts["wash_shuffle"] += t1 - t0
+        parts["papa_ema"] += t2 - t1
+        parts["wash_average"] += t3 - t2
+        t_spent += t3 - t0
+        passes += 1
+    return {
+        "value": cfg.P * passes / t_spent, "unit": "coords/s", "cores": 1, "kind": "oracle",
+        "sample": f"{passes} whole passes (shuffle + EMA + average) over the full config-{cfg.index} population, "
+                  f"{t_spent:.1f} s of CPU time",
+        "ms_per_step": t_spent / passes * 1e3,
+        "us_per_call": {k: v / passes * 1e6 for k, v in parts.items()},
+        "host_cores_available": os.cpu_count(),
+    }
+
+
+def load_traffic(workload_key, kernel):
+    """HBM bytes per launch measured with rocprofv3 --pmc (committed under profiles/)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload_key, {}).get(kernel)
+    except (OSError, ValueError):
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="1..5 (default 2: ResNet-18, N=5, p=0.001)")
+    ap.add_argument("--p", type=float, default=None, help="override the shuffle probability of every tensor")
+    ap.add_argument("--all-configs", action="store_true", help="also time the other configs (adds 'all_configs')")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-count", action="store_true", help="do not ask wash_shuffle for the selected count")
+    ap.add_argument("--only", choices=["pass", "copy"], default="pass",
+                    help="copy: run only the copy yardstick (for counter calibration)")
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path shards along P without any exchange; "
+              "no multi-GPU figure is produced). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2405_17517_amd as wash
+    from workloads import CONFIGS, get_config
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+
+    if args.only == "copy":
+        print(json.dumps({"copy_yardstick": copy_yardstick(torch, wash)}))
+        return
+
+    cfg = get_config(args.config)
+    main_res = run_config(torch, wash, cfg, args.steps, args.warmup, p_override=args.p, count=not args.no_count)
+    yard = copy_yardstick(torch, wash)
+
+    roof = main_res["roofline"]
+    dominant = max(roof, key=lambda k: roof[k]["avg_us"])
+    workload_key = f"config{cfg.index}" + (f"_p{args.p:g}" if args.p is not None else "")
+    r = roof[dominant]
+    roofline = {"kernel": dominant, "bound": "hbm", "achieved": r["achieved"], "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": r["frac"], "traffic": load_traffic(workload_key, dominant),
+                "alg_bytes_per_launch": r["alg_bytes"], "avg_us": r["avg_us"]}
+
+    line = {
+        "metric": "shuffle coords/s + effective HBM GB/s (% of roofline) at N models x P params",
+        "value": main_res["pass_coords_per_s"], "unit": "coords/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32 storage, u32 moves, f64 accumulation", "data": "synthetic",
+        "config": {"workload": f"config {cfg.index}: {cfg.name}, N={cfg.N}, P={cfg.P}, "
+                               f"{main_res['segments']} tensors, p={args.p if args.p is not None else 'as listed'}, "
+                               f"{'params+momentum' if cfg.momentum else 'params only'}; "
+                               "step = wash_shuffle + papa_ema + wash_average",
+                   "N": cfg.N, "P": cfg.P, "cache_resident": main_res["cache_resident"]},
+        "shuffle_coords_per_s": main_res["shuffle_coords_per_s"],
+        "selected_per_step": main_res["selected_per_step"],
+        "kernel_us": main_res["avg_us"], "kernel_median_us": main_res["median_us"],
+        "roofline": roofline,
+        "roofline_per_kernel": {k: {kk: vv for kk, vv in v.items()} | {"traffic": load_traffic(workload_key, k)}
+                                for k, v in roof.items()},
+        "copy_yardstick": yard,
+    }
+
+    if args.all_configs:
+        rows = []
+        for c in CONFIGS:
+            ps = c.p_sweep if c.p_sweep else (None,)
+            for p in ps:
+                k = min(args.steps, c.steps if not c.p_sweep else 20)
+                k = max(k, 5)
+                res = run_config(torch, wash, c, k, min(args.warmup, 3), p_override=p)
+                res["p_override"] = p
+                rows.append(res)
+                print(f"[bench] config {c.index} p={p} done: shuffle {res['avg_us']['wash_shuffle']:.1f} us, "
+                      f"ema {res['avg_us']['papa_ema']:.1f} us, avg {res['avg_us']['wash_average']:.1f} us",
+                      file=sys.stderr, flush=True)
+        line["all_configs"] = rows
+
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(cfg)
+    else:
+        line["cpu_baseline"] = None
+
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

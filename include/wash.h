@@ -126,6 +126,16 @@ int papa_ema(float *params, uint32_t N, uint64_t P, float alpha, void *stream);
  */
 int wash_layer_probs(double p, uint32_t L, int schedule, double *out);
 
+/*
+ * Measurement aid, not part of the method: dst[0..n) = src[0..n) with the same
+ * 16-byte streaming access the average and the EMA use.  It reads 4n and writes
+ * 4n bytes, which makes it the yardstick for the bandwidth a one-pass kernel
+ * reaches on this chip and the known-size kernel that calibrates the HBM
+ * traffic counters.   src, dst: device, n floats, not overlapping.
+ * Errors: WASH_EINVAL for NULL pointers, n = 0, overlap.
+ */
+int wash_copy_f32(const float *src, float *dst, uint64_t n, void *stream);
+
 /* Text for a status code (static storage, never NULL). */
 const char *wash_strerror(int status);
 

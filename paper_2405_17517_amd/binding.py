@@ -38,6 +38,8 @@ def _load():
     L.wash_average.restype = ctypes.c_int
     L.papa_ema.argtypes = [vp, u32, u64, ctypes.c_float, vp]
     L.papa_ema.restype = ctypes.c_int
+    L.wash_copy_f32.argtypes = [vp, vp, u64, vp]
+    L.wash_copy_f32.restype = ctypes.c_int
     L.wash_layer_probs.argtypes = [ctypes.c_double, u32, ctypes.c_int, vp]
     L.wash_layer_probs.restype = ctypes.c_int
     L.wash_strerror.argtypes = [ctypes.c_int]
@@ -129,6 +131,18 @@ def papa_ema(params: torch.Tensor, alpha: float) -> None:
     with torch.cuda.device(params.device):
         rc = _lib.papa_ema(params.data_ptr(), N, P, float(alpha), _stream(params))
     _check(rc, "papa_ema")
+
+
+def wash_copy_f32(src: torch.Tensor, dst: torch.Tensor) -> None:
+    """Plain streaming copy of a float32 buffer (bandwidth yardstick, see wash.h)."""
+    for t in (src, dst):
+        if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+            raise TypeError("need contiguous float32 GPU tensors")
+    if src.numel() != dst.numel() or src.device != dst.device:
+        raise TypeError("src and dst must have the same size and device")
+    with torch.cuda.device(src.device):
+        rc = _lib.wash_copy_f32(src.data_ptr(), dst.data_ptr(), src.numel(), _stream(src))
+    _check(rc, "wash_copy_f32")
 
 
 def wash_layer_probs(p: float, L: int, schedule: int = 0):

@@ -58,7 +58,7 @@ struct TableKey {
 
 struct Table {
     TableKey key;
-    void *dev = nullptr;            // [DevSegment x nsegs][uint32 x num_tiles]
+    void *dev = nullptr;            // [count slots][DevSegment x nsegs][uint32 x num_tiles]
     uint64_t num_tiles = 0;
 };
 
@@ -91,15 +91,16 @@ int get_table(int device, uint64_t P, uint32_t tile_coords, std::vector<wash::De
     const uint64_t num_tiles = (P + tile_coords - 1) / tile_coords;
     const size_t nsegs = key.segs.size();
     const size_t seg_bytes = nsegs * sizeof(wash::DevSegment);
-    const size_t bytes = seg_bytes + num_tiles * sizeof(uint32_t);
+    const size_t bytes = wash::kCountSlotBytes + seg_bytes + num_tiles * sizeof(uint32_t);
     std::vector<unsigned char> host;
     try {
         host.resize(bytes);
     } catch (const std::bad_alloc &) {
         return fail(WASH_ENOMEM, "segment table of %zu bytes", bytes);
     }
-    std::memcpy(host.data(), key.segs.data(), seg_bytes);
-    uint32_t *tile_first = reinterpret_cast<uint32_t *>(host.data() + seg_bytes);
+    std::memset(host.data(), 0, wash::kCountSlotBytes);
+    std::memcpy(host.data() + wash::kCountSlotBytes, key.segs.data(), seg_bytes);
+    uint32_t *tile_first = reinterpret_cast<uint32_t *>(host.data() + wash::kCountSlotBytes + seg_bytes);
     size_t s = 0;
     for (uint64_t t = 0; t < num_tiles; ++t) {
         const uint64_t begin = t * tile_coords;
@@ -201,9 +202,10 @@ int wash_shuffle(float *params, float *momentum, uint32_t N, uint64_t P, const w
     a.momentum = reinterpret_cast<uint32_t *>(momentum);
     a.N = N;
     a.P = P;
-    a.segs = static_cast<const wash::DevSegment *>(table->dev);
+    unsigned char *base = static_cast<unsigned char *>(table->dev);
+    a.segs = reinterpret_cast<const wash::DevSegment *>(base + wash::kCountSlotBytes);
     a.nsegs = static_cast<uint32_t>(table->key.segs.size());
-    a.tile_first = reinterpret_cast<const uint32_t *>(static_cast<const unsigned char *>(table->dev) +
+    a.tile_first = reinterpret_cast<const uint32_t *>(base + wash::kCountSlotBytes +
                                                       table->key.segs.size() * sizeof(wash::DevSegment));
     a.num_tiles = table->num_tiles;
     a.tile_coords = tile_coords;
@@ -211,6 +213,7 @@ int wash_shuffle(float *params, float *momentum, uint32_t N, uint64_t P, const w
     a.key_hi = static_cast<uint32_t>(seed >> 32);
     a.step = static_cast<uint32_t>(step);
     a.selected_count = reinterpret_cast<unsigned long long *>(selected_count);
+    a.count_slots = selected_count ? reinterpret_cast<unsigned long long *>(base) : nullptr;
     e = wash::launch_shuffle(a, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail_hip("wash_shuffle launch", e);
     return WASH_OK;
@@ -235,6 +238,17 @@ int papa_ema(float *params, uint32_t N, uint64_t P, float alpha, void *stream)
     if (!std::isfinite(alpha)) return fail(WASH_EINVAL, "alpha is not finite");
     const hipError_t e = wash::launch_ema(params, N, P, alpha, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail_hip("papa_ema launch", e);
+    return WASH_OK;
+}
+
+int wash_copy_f32(const float *src, float *dst, uint64_t n, void *stream)
+{
+    g_detail[0] = 0;
+    if (src == nullptr || dst == nullptr) return fail(WASH_EINVAL, "src or dst is NULL");
+    if (n == 0 || n > (1ull << 40)) return fail(WASH_EINVAL, "n must be in 1..2^40");
+    if (ranges_overlap(src, n * sizeof(float), dst, n * sizeof(float))) return fail(WASH_EINVAL, "dst overlaps src");
+    const hipError_t e = wash::launch_copy(src, dst, n, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip("wash_copy_f32 launch", e);
     return WASH_OK;
 }
 

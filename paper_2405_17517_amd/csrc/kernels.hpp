@@ -27,11 +27,18 @@ struct ShuffleArgs {
     uint32_t tile_coords;       // coordinates per tile (one wavefront scans one tile), multiple of 256
     uint32_t key_lo, key_hi;    // seed
     uint32_t step;
-    unsigned long long *selected_count; // or nullptr
+    unsigned long long *selected_count; // caller's counter, or nullptr
+    unsigned long long *count_slots;    // kCountSlots partial counters, all zero between calls; nullptr iff no counter
 };
+
+// Partial counters of the selected-coordinate statistic: one 128-byte line each.
+constexpr uint32_t kCountSlots = 256;
+constexpr uint32_t kCountSlotStride = 16;   // in 8-byte words
+constexpr size_t kCountSlotBytes = static_cast<size_t>(kCountSlots) * kCountSlotStride * 8;
 
 hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream);
 hipError_t launch_average(const float *params, float *out, uint32_t N, uint64_t P, hipStream_t stream);
+hipError_t launch_copy(const float *src, float *dst, uint64_t n, hipStream_t stream);
 hipError_t launch_ema(float *params, uint32_t N, uint64_t P, float alpha, hipStream_t stream);
 
 }  // namespace wash

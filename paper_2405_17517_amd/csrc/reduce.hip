@@ -103,6 +103,20 @@ __global__ __launch_bounds__(kThreads) void ema_kernel(float *__restrict__ param
     }
 }
 
+// Plain streaming copy: the yardstick for what a one-pass kernel can reach on this chip.
+__global__ __launch_bounds__(kThreads) void copy_kernel(const float *__restrict__ src, float *__restrict__ dst,
+                                                        uint64_t n)
+{
+    const uint64_t base = (static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4u;
+    if (base >= n) return;
+    if (base + 4u <= n) {
+        const f4u v = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(src + base));
+        __builtin_nontemporal_store(v, reinterpret_cast<f4u *>(dst + base));
+    } else {
+        for (uint64_t g = base; g < n; ++g) dst[g] = src[g];
+    }
+}
+
 inline bool grid_for(uint64_t P, dim3 &grid)
 {
     const uint64_t threads = (P + 3u) / 4u;
@@ -135,6 +149,14 @@ hipError_t run_ema(float *params, uint64_t P, double alpha, hipStream_t stream)
 #define WASH_FOR_EACH_N(X)                                                                         \
     X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17)   \
     X(18) X(19) X(20) X(21) X(22) X(23) X(24) X(25) X(26) X(27) X(28) X(29) X(30) X(31) X(32)
+
+hipError_t launch_copy(const float *src, float *dst, uint64_t n, hipStream_t stream)
+{
+    dim3 grid;
+    if (!grid_for(n, grid)) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(copy_kernel, grid, dim3(kThreads), 0, stream, src, dst, n);
+    return hipGetLastError();
+}
 
 hipError_t launch_average(const float *params, float *out, uint32_t N, uint64_t P, hipStream_t stream)
 {

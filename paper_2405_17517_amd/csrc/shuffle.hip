@@ -11,7 +11,8 @@
 //            runs on dense lanes and HBM traffic follows p*N*P, not N*P.
 //   permute  whenever 64 coordinates are queued (and once at the end) each
 //            lane takes one coordinate: its N values (and N momentum values)
-//            are gathered into an LDS slab [N][64], the descending
+//            are gathered into an LDS slab [N][64] by direct global-to-LDS
+//            loads (all N in flight, no register array), the descending
 //            Fisher-Yates walk swaps slab rows in place, and because slot i is
 //            final after step i its value is stored to row i right there.
 // Everything random is integer arithmetic, so the result is bit-identical to
@@ -44,6 +45,17 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+typedef __attribute__((address_space(1))) const void *global_cptr;
+typedef __attribute__((address_space(3))) void *lds_ptr;
+
+// One dword per active lane straight from global memory into LDS at row[lane]
+// (no VGPR in between): the N gathers of a batch are all in flight at once
+// whatever N is, and the slab is filled without a register array.
+__device__ __forceinline__ void gather_row_to_lds(const uint32_t *src, uint32_t *row)
+{
+    __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)row, 4, 0, 0);
+}
+
 // Gather, permute and scatter up to 64 queued coordinates, one per lane.
 template <bool kMomentum>
 __device__ __forceinline__ void permute_batch(const ShuffleArgs &a, uint64_t tile_begin,
@@ -59,11 +71,11 @@ __device__ __forceinline__ void permute_batch(const ShuffleArgs &a, uint64_t til
     uint32_t *col_m = kMomentum ? a.momentum + g : nullptr;
 
     // gather the column(s) into the slab: slab[n][lane]
-#pragma unroll 8
     for (uint32_t n = 0; n < N; ++n) {
-        slab[n * kWave + lane] = col[static_cast<uint64_t>(n) * P];
-        if (kMomentum) slab_m[n * kWave + lane] = col_m[static_cast<uint64_t>(n) * P];
+        gather_row_to_lds(col + static_cast<uint64_t>(n) * P, slab + n * kWave);
+        if (kMomentum) gather_row_to_lds(col_m + static_cast<uint64_t>(n) * P, slab_m + n * kWave);
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // descending Fisher-Yates on the values themselves: swapping slab rows i and j keeps
     // slab[n] == old[perm[n]]; row i is final after step i and goes straight to memory
@@ -99,7 +111,8 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
     extern __shared__ uint32_t lds[];
     const uint32_t lane = lane_id();
     const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const uint64_t tile = static_cast<uint64_t>(blockIdx.x) * kWavesPerBlock + wave_in_block;
+    const uint32_t waves_per_block = blockDim.x / kWave;
+    const uint64_t tile = static_cast<uint64_t>(blockIdx.x) * waves_per_block + wave_in_block;
     if (tile >= a.num_tiles) return;
     const uint32_t first = a.tile_first[tile];
     if (first == kNoSegment) return;
@@ -146,12 +159,16 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
         }
         if (__ballot(sel[0] | sel[1] | sel[2] | sel[3]) == 0) continue;
 
+        // append in ascending coordinate order (lane-major, then k), so that neighbours in the
+        // queue are neighbours in memory and a batch touches as few cache lines as possible
+        const uint64_t b0 = __ballot(sel[0]), b1 = __ballot(sel[1]), b2 = __ballot(sel[2]), b3 = __ballot(sel[3]);
+        uint32_t pos = queued + lanes_below(b0) + lanes_below(b1) + lanes_below(b2) + lanes_below(b3);
+        const uint32_t off0 = static_cast<uint32_t>(g0 - tile_begin);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const uint64_t m = __ballot(sel[k]);
-            if (sel[k]) queue[queued + lanes_below(m)] = static_cast<uint32_t>(g0 + k - tile_begin);
-            queued += __popcll(m);
+            if (sel[k]) queue[pos++] = off0 + k;
         }
+        queued += __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3);
         while (queued >= kWave) {
             wave_lds_sync();
             permute_batch<kMomentum>(a, tile_begin, queue + (queued - kWave), kWave, slab, slab_m);
@@ -165,8 +182,28 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
         permute_batch<kMomentum>(a, tile_begin, queue, queued, slab, slab_m);
         selected += queued;
     }
-    if (a.selected_count != nullptr && selected != 0 && lane == 0)
-        atomicAdd(a.selected_count, static_cast<unsigned long long>(selected));
+    // One atomic per wavefront on a single address would serialise the whole grid at the
+    // memory side; spread them over kCountSlots cache lines and let a tiny kernel fold them.
+    if (a.count_slots != nullptr && selected != 0 && lane == 0)
+        atomicAdd(a.count_slots + (tile % kCountSlots) * kCountSlotStride, static_cast<unsigned long long>(selected));
+}
+
+// Adds the per-slot partial counts to the caller's counter and clears the slots for the next call.
+__global__ __launch_bounds__(kCountSlots) void fold_count_kernel(unsigned long long *slots,
+                                                                 unsigned long long *selected_count)
+{
+    __shared__ unsigned long long partial[kCountSlots / kWave];
+    unsigned long long v = slots[threadIdx.x * kCountSlotStride];
+    if (v != 0) slots[threadIdx.x * kCountSlotStride] = 0;
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
+    if ((threadIdx.x % kWave) == 0) partial[threadIdx.x / kWave] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long total = 0;
+        for (uint32_t w = 0; w < kCountSlots / kWave; ++w) total += partial[w];
+        if (total != 0) atomicAdd(selected_count, total);
+    }
 }
 
 }  // namespace
@@ -174,15 +211,22 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
 hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream)
 {
     if (a.num_tiles == 0 || a.nsegs == 0) return hipSuccess;
-    const uint64_t blocks64 = (a.num_tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    // the direct-to-LDS loads address LDS through a 16-bit offset: keep a block's partition below 64 KiB
+    const size_t per_wave = (kQueueCap + static_cast<size_t>(a.N) * kWave * (a.momentum ? 2 : 1)) * sizeof(uint32_t);
+    uint32_t waves = kWavesPerBlock;
+    while (waves > 1 && per_wave * waves > 65536) waves >>= 1;
+    if (per_wave * waves > 65536) return hipErrorInvalidConfiguration;
+    const uint64_t blocks64 = (a.num_tiles + waves - 1) / waves;
     if (blocks64 > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
-    const dim3 grid(static_cast<uint32_t>(blocks64)), block(kWave * kWavesPerBlock);
-    const size_t per_wave = kQueueCap + static_cast<size_t>(a.N) * kWave * (a.momentum ? 2 : 1);
-    const size_t lds_bytes = per_wave * kWavesPerBlock * sizeof(uint32_t);
+    const dim3 grid(static_cast<uint32_t>(blocks64)), block(kWave * waves);
+    const size_t lds_bytes = per_wave * waves;
     if (a.momentum)
         hipLaunchKernelGGL(shuffle_kernel<true>, grid, block, lds_bytes, stream, a);
     else
         hipLaunchKernelGGL(shuffle_kernel<false>, grid, block, lds_bytes, stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || a.count_slots == nullptr) return e;
+    hipLaunchKernelGGL(fold_count_kernel, dim3(1), dim3(kCountSlots), 0, stream, a.count_slots, a.selected_count);
     return hipGetLastError();
 }
 
