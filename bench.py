@@ -192,13 +192,18 @@ def cpu_baseline(cfg, budget_s=20.0):
 
 
 def load_traffic(workload_key, kernel):
-    """HBM bytes per launch measured with rocprofv3 --pmc (committed under profiles/)."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    """HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE in separate
+    runs of this script (summaries committed under profiles/); None if that workload was not profiled."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     try:
         with open(path) as f:
-            return json.load(f).get(workload_key, {}).get(kernel)
+            for line in f:
+                parts = line.split()
+                if len(parts) == 3 and parts[0] == workload_key and parts[1] == kernel:
+                    return float(parts[2])
     except (OSError, ValueError):
-        return None
+        pass
+    return None
 
 
 def main():
