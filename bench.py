@@ -216,6 +216,9 @@ def main():
     ap.add_argument("--all-configs", action="store_true", help="also time the other configs (adds 'all_configs')")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-count", action="store_true", help="do not ask wash_shuffle for the selected count")
+    ap.add_argument("--stream-min-bytes", type=int, default=None,
+                    help="override the population size from which average/EMA use non-temporal accesses")
+    ap.add_argument("--tile-coords", type=int, default=None, help="override the shuffle tile size")
     ap.add_argument("--only", choices=["pass", "copy"], default="pass",
                     help="copy: run only the copy yardstick (for counter calibration)")
     args = ap.parse_args()
@@ -233,6 +236,11 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+
+    if args.stream_min_bytes is not None:
+        wash.wash_set_option(wash.OPT_STREAM_MIN_BYTES, args.stream_min_bytes)
+    if args.tile_coords is not None:
+        wash.wash_set_option(wash.OPT_TILE_COORDS, args.tile_coords)
 
     if args.only == "copy":
         print(json.dumps({"copy_yardstick": copy_yardstick(torch, wash)}))

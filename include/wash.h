@@ -147,8 +147,12 @@ const char *wash_last_error_detail(void);
  * on them).  Returns WASH_EINVAL for an unknown option or a value out of range.
  *   WASH_OPT_TILE_COORDS  coordinates scanned by one wavefront in wash_shuffle;
  *                         a multiple of 256 in [256, 65536], or 0 = choose by P
+ *   WASH_OPT_STREAM_MIN_BYTES  papa_ema uses non-temporal (cache-bypassing) accesses when the
+ *                         population N*P*4 is at least this many bytes (default 256 MiB;
+ *                         smaller populations are left to the 256 MB Infinity Cache)
  */
 #define WASH_OPT_TILE_COORDS 1
+#define WASH_OPT_STREAM_MIN_BYTES 2
 int wash_set_option(int option, int64_t value);
 
 /* Free the cached device tables of every device (waits for the devices). */

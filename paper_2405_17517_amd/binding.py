@@ -15,6 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libwash_hip.so")
 MAX_N = 32
 OPT_TILE_COORDS = 1
+OPT_STREAM_MIN_BYTES = 2
 
 
 class WashError(RuntimeError):

@@ -66,6 +66,7 @@ std::mutex g_mutex;
 std::list<Table> g_tables;          // most recently used first
 constexpr size_t kMaxTables = 16;
 int64_t g_tile_coords_option = 0;   // 0 = choose by P
+int64_t g_stream_min_bytes = 256ll << 20;  // papa_ema on populations at least this large uses non-temporal accesses
 
 uint32_t choose_tile_coords(uint64_t P)
 {
@@ -236,7 +237,8 @@ int papa_ema(float *params, uint32_t N, uint64_t P, float alpha, void *stream)
     g_detail[0] = 0;
     if (int rc = check_population(params, N, P)) return rc;
     if (!std::isfinite(alpha)) return fail(WASH_EINVAL, "alpha is not finite");
-    const hipError_t e = wash::launch_ema(params, N, P, alpha, static_cast<hipStream_t>(stream));
+    const bool nt = static_cast<int64_t>(N * P * sizeof(float)) >= g_stream_min_bytes;
+    const hipError_t e = wash::launch_ema(params, N, P, alpha, nt, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail_hip("papa_ema launch", e);
     return WASH_OK;
 }
@@ -292,6 +294,12 @@ int wash_set_option(int option, int64_t value)
             return fail(WASH_EINVAL, "tile coordinates must be 0 or a multiple of 256 in [256, 65536]");
         std::lock_guard<std::mutex> lock(g_mutex);
         g_tile_coords_option = value;
+        return WASH_OK;
+    }
+    if (option == WASH_OPT_STREAM_MIN_BYTES) {
+        if (value < 0) return fail(WASH_EINVAL, "byte threshold must be >= 0");
+        std::lock_guard<std::mutex> lock(g_mutex);
+        g_stream_min_bytes = value;
         return WASH_OK;
     }
     return fail(WASH_EINVAL, "unknown option %d", option);

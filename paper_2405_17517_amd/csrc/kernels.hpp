@@ -39,6 +39,6 @@ constexpr size_t kCountSlotBytes = static_cast<size_t>(kCountSlots) * kCountSlot
 hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream);
 hipError_t launch_average(const float *params, float *out, uint32_t N, uint64_t P, hipStream_t stream);
 hipError_t launch_copy(const float *src, float *dst, uint64_t n, hipStream_t stream);
-hipError_t launch_ema(float *params, uint32_t N, uint64_t P, float alpha, hipStream_t stream);
+hipError_t launch_ema(float *params, uint32_t N, uint64_t P, float alpha, bool nontemporal, hipStream_t stream);
 
 }  // namespace wash

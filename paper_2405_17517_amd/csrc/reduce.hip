@@ -19,6 +19,22 @@ constexpr int kThreads = 256;
 
 typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
 
+// Non-temporal accesses stream past the caches.  The average always uses them (it never
+// re-reads anything).  The in-place EMA uses them once the population exceeds the 256 MB
+// Infinity Cache; below that, plain accesses let its stores hit the lines its loads brought in.
+template <bool NT>
+__device__ __forceinline__ f4u load4(const float *p)
+{
+    if (NT) return __builtin_nontemporal_load(reinterpret_cast<const f4u *>(p));
+    return *reinterpret_cast<const f4u *>(p);
+}
+template <bool NT>
+__device__ __forceinline__ void store4(float *p, f4u v)
+{
+    if (NT) __builtin_nontemporal_store(v, reinterpret_cast<f4u *>(p));
+    else *reinterpret_cast<f4u *>(p) = v;
+}
+
 // fp64 arithmetic is kept unfused so that it matches the definition operation by operation
 #pragma clang fp contract(off)
 
@@ -33,7 +49,7 @@ __global__ __launch_bounds__(kThreads) void average_kernel(const float *__restri
         f4u v[N];
 #pragma unroll
         for (int n = 0; n < N; ++n)
-            v[n] = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(params + static_cast<uint64_t>(n) * P + base));
+            v[n] = load4<true>(params + static_cast<uint64_t>(n) * P + base);
         double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
 #pragma unroll
         for (int n = 0; n < N; ++n) {
@@ -47,7 +63,7 @@ __global__ __launch_bounds__(kThreads) void average_kernel(const float *__restri
         o.y = static_cast<float>(s1 / inv_den);
         o.z = static_cast<float>(s2 / inv_den);
         o.w = static_cast<float>(s3 / inv_den);
-        __builtin_nontemporal_store(o, reinterpret_cast<f4u *>(out + base));
+        store4<true>(out + base, o);
     } else {
         for (uint64_t g = base; g < P; ++g) {
             double s = 0.0;
@@ -58,7 +74,7 @@ __global__ __launch_bounds__(kThreads) void average_kernel(const float *__restri
     }
 }
 
-template <int N>
+template <int N, bool NT>
 __global__ __launch_bounds__(kThreads) void ema_kernel(float *__restrict__ params, uint64_t P, double alpha)
 {
     const uint64_t base = (static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4u;
@@ -69,7 +85,7 @@ __global__ __launch_bounds__(kThreads) void ema_kernel(float *__restrict__ param
         f4u v[N];
 #pragma unroll
         for (int n = 0; n < N; ++n)
-            v[n] = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(params + static_cast<uint64_t>(n) * P + base));
+            v[n] = load4<NT>(params + static_cast<uint64_t>(n) * P + base);
         double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
 #pragma unroll
         for (int n = 0; n < N; ++n) {
@@ -86,7 +102,7 @@ __global__ __launch_bounds__(kThreads) void ema_kernel(float *__restrict__ param
             o.y = static_cast<float>(alpha * static_cast<double>(v[n].y) + m1);
             o.z = static_cast<float>(alpha * static_cast<double>(v[n].z) + m2);
             o.w = static_cast<float>(alpha * static_cast<double>(v[n].w) + m3);
-            __builtin_nontemporal_store(o, reinterpret_cast<f4u *>(params + static_cast<uint64_t>(n) * P + base));
+            store4<NT>(params + static_cast<uint64_t>(n) * P + base, o);
         }
     } else {
         for (uint64_t g = base; g < P; ++g) {
@@ -136,11 +152,12 @@ hipError_t run_average(const float *params, float *out, uint64_t P, hipStream_t 
 }
 
 template <int N>
-hipError_t run_ema(float *params, uint64_t P, double alpha, hipStream_t stream)
+hipError_t run_ema(float *params, uint64_t P, double alpha, bool nt, hipStream_t stream)
 {
     dim3 grid;
     if (!grid_for(P, grid)) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL(ema_kernel<N>, grid, dim3(kThreads), 0, stream, params, P, alpha);
+    if (nt) hipLaunchKernelGGL((ema_kernel<N, true>), grid, dim3(kThreads), 0, stream, params, P, alpha);
+    else hipLaunchKernelGGL((ema_kernel<N, false>), grid, dim3(kThreads), 0, stream, params, P, alpha);
     return hipGetLastError();
 }
 
@@ -168,10 +185,10 @@ hipError_t launch_average(const float *params, float *out, uint32_t N, uint64_t 
     }
 }
 
-hipError_t launch_ema(float *params, uint32_t N, uint64_t P, float alpha, hipStream_t stream)
+hipError_t launch_ema(float *params, uint32_t N, uint64_t P, float alpha, bool nt, hipStream_t stream)
 {
     switch (N) {
-#define X(n) case n: return run_ema<n>(params, P, static_cast<double>(alpha), stream);
+#define X(n) case n: return run_ema<n>(params, P, static_cast<double>(alpha), nt, stream);
         WASH_FOR_EACH_N(X)
 #undef X
     default: return hipErrorInvalidValue;
