@@ -46,6 +46,22 @@ def lib():
         L.wash_shuffle_ref.restype = ctypes.c_int
         L.wash_shuffle_ref_mt.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp, u32]
         L.wash_shuffle_ref_mt.restype = ctypes.c_int
+        L.wash_ref_log2.argtypes = [dbl]
+        L.wash_ref_log2.restype = dbl
+        L.wash_ref_gap_scale.argtypes = [dbl]
+        L.wash_ref_gap_scale.restype = dbl
+        L.wash_ref_gap_uniform.argtypes = [u64, u64, u64, u32]
+        L.wash_ref_gap_uniform.restype = u64
+        L.wash_ref_gap.argtypes = [u64, dbl]
+        L.wash_ref_gap.restype = u32
+        L.wash_shuffle_gap_ref_window.argtypes = [vp, vp, u32, u64, u64, u64, u64, vp, u32, u64, u64, vp]
+        L.wash_shuffle_gap_ref_window.restype = ctypes.c_int
+        L.wash_shuffle_gap_ref.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp]
+        L.wash_shuffle_gap_ref.restype = ctypes.c_int
+        L.wash_shuffle_gap_ref_mt.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp, u32]
+        L.wash_shuffle_gap_ref_mt.restype = ctypes.c_int
+        L.wash_ref_gap_mask.argtypes = [vp, u64, vp, u32, u64, u64]
+        L.wash_ref_gap_mask.restype = ctypes.c_int
         L.wash_average_ref.argtypes = [vp, vp, u32, u64]
         L.wash_average_ref.restype = ctypes.c_int
         L.papa_ema_ref.argtypes = [vp, u32, u64, ctypes.c_float]
@@ -114,8 +130,35 @@ def layer_probs(p, L, schedule=0):
     return out[:L]
 
 
-def shuffle(params, momentum, segs, seed, step, threads=1):
-    """In-place shuffle of a whole [N, P] population. Returns the selected count."""
+def log2(x):
+    return float(lib().wash_ref_log2(float(x)))
+
+
+def gap_scale(p):
+    return float(lib().wash_ref_gap_scale(float(p)))
+
+
+def gap_uniform(seed, step, s, d):
+    return int(lib().wash_ref_gap_uniform(seed, step, s, d))
+
+
+def gap(U, inv):
+    return int(lib().wash_ref_gap(int(U), float(inv)))
+
+
+def gap_mask(P, segs, seed, step):
+    """uint8 [P]: 1 where the gap stream selects the coordinate."""
+    mask = np.zeros(P, dtype=np.uint8)
+    sa = _segarray(segs)
+    rc = lib().wash_ref_gap_mask(mask.ctypes.data, P, ctypes.addressof(sa), len(segs), seed, step)
+    if rc != 0:
+        raise ValueError("wash_ref_gap_mask: invalid argument")
+    return mask
+
+
+def shuffle(params, momentum, segs, seed, step, threads=1, stream="v1"):
+    """In-place shuffle of a whole [N, P] population. Returns the selected count.
+    stream: "v1" (one mask word per coordinate) or "gap" (geometric gap sampling)."""
     _check_pop(params, "params")
     N, P = params.shape
     if momentum is not None:
@@ -124,20 +167,24 @@ def shuffle(params, momentum, segs, seed, step, threads=1):
     sa = _segarray(segs)
     cnt = ctypes.c_uint64(0)
     mom = momentum.ctypes.data if momentum is not None else None
+    if stream not in ("v1", "gap"):
+        raise ValueError("stream must be 'v1' or 'gap'")
+    one = lib().wash_shuffle_ref if stream == "v1" else lib().wash_shuffle_gap_ref
+    many = lib().wash_shuffle_ref_mt if stream == "v1" else lib().wash_shuffle_gap_ref_mt
     if threads <= 1:
-        rc = lib().wash_shuffle_ref(params.ctypes.data, mom, N, P, ctypes.addressof(sa), len(segs),
-                                    seed, step, ctypes.addressof(cnt))
+        rc = one(params.ctypes.data, mom, N, P, ctypes.addressof(sa), len(segs), seed, step, ctypes.addressof(cnt))
     else:
-        rc = lib().wash_shuffle_ref_mt(params.ctypes.data, mom, N, P, ctypes.addressof(sa), len(segs),
-                                       seed, step, ctypes.addressof(cnt), threads)
+        rc = many(params.ctypes.data, mom, N, P, ctypes.addressof(sa), len(segs), seed, step,
+                  ctypes.addressof(cnt), threads)
     if rc != 0:
         raise ValueError(f"wash_shuffle_ref: invalid argument (rc={rc})")
     return cnt.value
 
 
-def shuffle_window(win, mom_win, P, g_begin, segs, seed, step):
+def shuffle_window(win, mom_win, P, g_begin, segs, seed, step, stream="v1"):
     """In-place shuffle of a window holding columns [g_begin, g_begin + W) of a
-    population with P columns; win is a contiguous [N, W] array."""
+    population with P columns; win is a contiguous [N, W] array.  For the gap
+    stream the window must start and end on multiples of 1024 (or at P)."""
     _check_pop(win, "win")
     N, W = win.shape
     if mom_win is not None:
@@ -146,8 +193,9 @@ def shuffle_window(win, mom_win, P, g_begin, segs, seed, step):
     sa = _segarray(segs)
     cnt = ctypes.c_uint64(0)
     mom = mom_win.ctypes.data if mom_win is not None else None
-    rc = lib().wash_shuffle_ref_window(win.ctypes.data, mom, N, P, W, g_begin, g_begin + W,
-                                       ctypes.addressof(sa), len(segs), seed, step, ctypes.addressof(cnt))
+    fn = lib().wash_shuffle_ref_window if stream == "v1" else lib().wash_shuffle_gap_ref_window
+    rc = fn(win.ctypes.data, mom, N, P, W, g_begin, g_begin + W,
+            ctypes.addressof(sa), len(segs), seed, step, ctypes.addressof(cnt))
     if rc != 0:
         raise ValueError(f"wash_shuffle_ref_window: invalid argument (rc={rc})")
     return cnt.value

@@ -11,7 +11,7 @@ LIB = os.path.join(HERE, "libwash_ref.so")
 def build(force: bool = True) -> str:
     if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
         return LIB
-    cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-Wextra", "-fPIC", "-shared", "-pthread",
+    cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-Wall", "-Wextra", "-fPIC", "-shared", "-pthread",
            SRC, "-o", LIB, "-lm"]
     subprocess.run(cmd, check=True)
     return LIB

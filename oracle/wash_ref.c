@@ -224,6 +224,201 @@ int wash_shuffle_ref(float *params, float *momentum, uint32_t N, uint64_t P,
 }
 
 /* ------------------------------------------------------------------------ */
+/*
+ * The same shuffle step with a second mask stream, "gap" (stream v2).
+ *
+ * Law: identical to Eq. 3 -- every coordinate of a segment is selected
+ * independently with the segment's probability p, then permuted by pi_g exactly
+ * as above.  Only the way the Bernoulli mask is drawn differs: instead of one
+ * draw per coordinate, the distances between successive selected coordinates
+ * are drawn.  For iid Bernoulli(p) trials the number of trials up to and
+ * including the next success is geometric, P(gap > k) = (1-p)^k, and by
+ * inversion  gap = 1 + floor(log2(u) / log2(1-p))  for u uniform on (0, 1].
+ * Because the geometric law has no memory, restarting the walk at fixed places
+ * leaves the trials iid; the walk restarts at every multiple of 1024
+ * coordinates and at every segment start, which makes the stream addressable
+ * (a piece depends on nothing before it).  The work is proportional to the
+ * number of selected coordinates instead of the number of coordinates.
+ *
+ * Definition (this repository's own; the paper fixes the law only):
+ *   - zero-length segments are dropped and neighbours that touch and have the
+ *     same p (same double) are merged; segments with p = 0 select nothing;
+ *   - a merged segment [a, b) is cut into pieces [s, e) at the multiples of 1024;
+ *   - in a piece, pos = s - 1; for d = 0, 1, 2, ...:
+ *       U_d  = the top 53 bits of the 64-bit number (hi = word 2(d mod 2),
+ *              lo = word 2(d mod 2)+1) of Philox(key, (lo32(s), hi32(s),
+ *              lo32(step), 0x80000000 + d/2));
+ *       gap  = 1 + floor((wash_ref_log2(U_d + 1) - 53) * inv), capped at 2048,
+ *              inv = 1 / wash_ref_log2(1 - p)  (inv = 0 for p = 1);
+ *       pos += gap; stop if pos >= e; coordinate pos is selected.
+ *   - pi_g and the gather are those of stream v1.
+ * wash_ref_log2 is a fixed sequence of IEEE double operations (below), so that
+ * another implementation can reproduce it bit for bit.
+ */
+#define WASH_REF_PIECE 1024u
+
+/* log2 of a positive finite normal double, as a fixed sequence of IEEE
+   operations: split x = m * 2^e with m in (sqrt(1/2), sqrt(2)], then
+   ln m = 2 atanh(s), s = (m-1)/(m+1), by its odd series up to s^21. */
+double wash_ref_log2(double x)
+{
+    uint64_t bits;
+    memcpy(&bits, &x, sizeof bits);
+    int e = (int)((bits >> 52) & 0x7FFu) - 1023;
+    bits = (bits & 0x000FFFFFFFFFFFFFull) | 0x3FF0000000000000ull;
+    double m;
+    memcpy(&m, &bits, sizeof m);
+    if (m > 1.4142135623730951) { m = m * 0.5; e += 1; }
+    double s = (m - 1.0) / (m + 1.0);
+    double z = s * s;
+    double poly = 1.0 / 21.0;
+    poly = poly * z + 1.0 / 19.0;
+    poly = poly * z + 1.0 / 17.0;
+    poly = poly * z + 1.0 / 15.0;
+    poly = poly * z + 1.0 / 13.0;
+    poly = poly * z + 1.0 / 11.0;
+    poly = poly * z + 1.0 / 9.0;
+    poly = poly * z + 1.0 / 7.0;
+    poly = poly * z + 1.0 / 5.0;
+    poly = poly * z + 1.0 / 3.0;
+    poly = poly * z + 1.0;
+    double t = s * poly;
+    double ln_m = t + t;
+    return (double)e + ln_m * 1.4426950408889634;
+}
+
+/* 1 / log2(1 - p) for 0 < p < 1 (negative); 0 for p = 1. */
+double wash_ref_gap_scale(double p)
+{
+    if (p >= 1.0) return 0.0;
+    return 1.0 / wash_ref_log2(1.0 - p);
+}
+
+/* The d-th 53-bit uniform of the piece that starts at coordinate s. */
+uint64_t wash_ref_gap_uniform(uint64_t seed, uint64_t step, uint64_t s, uint32_t d)
+{
+    uint32_t ctr[4] = { (uint32_t)s, (uint32_t)(s >> 32), (uint32_t)step, 0x80000000u + (d >> 1) };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    wash_ref_philox4x32_10(ctr, key, out);
+    uint64_t w = ((uint64_t)out[2u * (d & 1u)] << 32) | (uint64_t)out[2u * (d & 1u) + 1u];
+    return w >> 11;
+}
+
+/* Geometric gap (>= 1, capped at 2048) from a 53-bit uniform U and inv = 1/log2(1-p). */
+uint32_t wash_ref_gap(uint64_t U, double inv)
+{
+    double L = wash_ref_log2((double)(U + 1u)) - 53.0; /* log2 of u = (U+1)/2^53, in [-53, 0] */
+    double q = L * inv;                                /* >= 0 */
+    if (!(q < 2047.0)) q = 2047.0;
+    return 1u + (uint32_t)floor(q);
+}
+
+/* Walks the gap stream over the pieces that start inside [g_begin, g_end) and calls
+   visit(ctx, g) for every selected coordinate g, in ascending order. */
+typedef void (*gap_visit_fn)(void *ctx, uint64_t g);
+
+static void gap_walk(uint64_t g_begin, uint64_t g_end, const wash_ref_segment *segs, uint32_t nsegs,
+                     uint64_t seed, uint64_t step, gap_visit_fn visit, void *ctx)
+{
+    uint32_t k = 0;
+    while (k < nsegs) {
+        /* next merged segment [a, b) with probability p */
+        while (k < nsegs && segs[k].length == 0) ++k;
+        if (k == nsegs) break;
+        uint64_t a = segs[k].offset, b = segs[k].offset + segs[k].length;
+        double p = segs[k].p;
+        ++k;
+        while (k < nsegs && (segs[k].length == 0 || (segs[k].offset == b && segs[k].p == p))) {
+            if (segs[k].length != 0) b = segs[k].offset + segs[k].length;
+            ++k;
+        }
+        if (p == 0.0) continue;
+        double inv = wash_ref_gap_scale(p);
+
+        for (uint64_t s = a; s < b; ) {
+            uint64_t e = (s / WASH_REF_PIECE + 1u) * WASH_REF_PIECE; /* next multiple of 1024 */
+            if (e > b) e = b;
+            if (s >= g_begin && s < g_end) {
+                uint64_t pos = s - 1u; /* wraps for s = 0; the first gap (>= 1) brings it back */
+                for (uint32_t d = 0;; ++d) {
+                    pos += wash_ref_gap(wash_ref_gap_uniform(seed, step, s, d), inv);
+                    if (pos >= e) break;
+                    visit(ctx, pos);
+                }
+            }
+            s = e;
+        }
+    }
+}
+
+static int gap_window_ok(uint64_t P, uint64_t g_begin, uint64_t g_end)
+{
+    /* pieces are whole inside or outside a window only if it is cut on the piece grid */
+    if (g_begin > g_end || g_end > P) return 0;
+    if (g_begin % WASH_REF_PIECE != 0) return 0;
+    if (g_end % WASH_REF_PIECE != 0 && g_end != P) return 0;
+    return 1;
+}
+
+typedef struct {
+    uint32_t *vals, *moms;
+    uint32_t N;
+    uint64_t row_stride, g_begin, seed, step, count;
+} gap_shuffle_ctx;
+
+static void gap_shuffle_visit(void *vctx, uint64_t g)
+{
+    gap_shuffle_ctx *c = (gap_shuffle_ctx *)vctx;
+    uint32_t perm[WASH_REF_MAX_N], old[WASH_REF_MAX_N];
+    ++c->count;
+    wash_ref_permutation(c->seed, c->step, g, c->N, perm);   /* pi_g as in stream v1 */
+    uint64_t col = g - c->g_begin;
+    for (uint32_t n = 0; n < c->N; ++n) old[n] = c->vals[(uint64_t)n * c->row_stride + col];
+    for (uint32_t n = 0; n < c->N; ++n) c->vals[(uint64_t)n * c->row_stride + col] = old[perm[n]];
+    if (c->moms != NULL) {
+        for (uint32_t n = 0; n < c->N; ++n) old[n] = c->moms[(uint64_t)n * c->row_stride + col];
+        for (uint32_t n = 0; n < c->N; ++n) c->moms[(uint64_t)n * c->row_stride + col] = old[perm[n]];
+    }
+}
+
+int wash_shuffle_gap_ref_window(float *params, float *momentum, uint32_t N, uint64_t P,
+                                uint64_t row_stride, uint64_t g_begin, uint64_t g_end,
+                                const wash_ref_segment *segs, uint32_t nsegs,
+                                uint64_t seed, uint64_t step, uint64_t *selected_count)
+{
+    if (params == NULL || N == 0 || N > WASH_REF_MAX_N || P == 0) return -1;
+    if (step >= 4294967296ull || !gap_window_ok(P, g_begin, g_end)) return -1;
+    if (nsegs > 0 && segs == NULL) return -1;
+    if (check_segments(P, segs, nsegs) != 0) return -1;
+    gap_shuffle_ctx c = { (uint32_t *)params, (uint32_t *)momentum, N, row_stride, g_begin, seed, step, 0 };
+    gap_walk(g_begin, g_end, segs, nsegs, seed, step, gap_shuffle_visit, &c);
+    if (selected_count != NULL) *selected_count += c.count;
+    return 0;
+}
+
+/* The Bernoulli mask of the gap stream alone: mask[g] = 1 for every selected g, else untouched. */
+static void gap_mask_visit(void *vctx, uint64_t g) { ((uint8_t *)vctx)[g] = 1u; }
+
+int wash_ref_gap_mask(uint8_t *mask, uint64_t P, const wash_ref_segment *segs, uint32_t nsegs,
+                      uint64_t seed, uint64_t step)
+{
+    if (mask == NULL || P == 0 || step >= 4294967296ull) return -1;
+    if (nsegs > 0 && segs == NULL) return -1;
+    if (check_segments(P, segs, nsegs) != 0) return -1;
+    gap_walk(0, P, segs, nsegs, seed, step, gap_mask_visit, mask);
+    return 0;
+}
+
+int wash_shuffle_gap_ref(float *params, float *momentum, uint32_t N, uint64_t P,
+                         const wash_ref_segment *segs, uint32_t nsegs,
+                         uint64_t seed, uint64_t step, uint64_t *selected_count)
+{
+    return wash_shuffle_gap_ref_window(params, momentum, N, P, P, 0, P, segs, nsegs, seed, step,
+                                       selected_count);
+}
+
+/* ------------------------------------------------------------------------ */
 /* Uniform average and PAPA EMA: the definitions in fp64, rounded once.      */
 
 int wash_average_ref(const float *params, float *out, uint32_t N, uint64_t P)
@@ -269,6 +464,7 @@ typedef struct {
     uint32_t nsegs;
     uint64_t seed, step, count;
     int status;
+    int gap_stream;
 } shuffle_job;
 
 static void *shuffle_job_run(void *arg)
@@ -278,17 +474,23 @@ static void *shuffle_job_run(void *arg)
     /* the window here is the whole population (stride P, columns from 0), but
        only coordinates in [g_begin, g_end) are visited */
     if (j->g_begin == j->g_end) { j->status = 0; return NULL; }
-    j->status = wash_shuffle_ref_window(j->params + j->g_begin,
-                                        j->momentum ? j->momentum + j->g_begin : NULL,
-                                        j->N, j->P, j->P, j->g_begin, j->g_end,
-                                        j->segs, j->nsegs, j->seed, j->step, &j->count);
+    if (j->gap_stream)
+        j->status = wash_shuffle_gap_ref_window(j->params + j->g_begin,
+                                                j->momentum ? j->momentum + j->g_begin : NULL,
+                                                j->N, j->P, j->P, j->g_begin, j->g_end,
+                                                j->segs, j->nsegs, j->seed, j->step, &j->count);
+    else
+        j->status = wash_shuffle_ref_window(j->params + j->g_begin,
+                                            j->momentum ? j->momentum + j->g_begin : NULL,
+                                            j->N, j->P, j->P, j->g_begin, j->g_end,
+                                            j->segs, j->nsegs, j->seed, j->step, &j->count);
     return NULL;
 }
 
-int wash_shuffle_ref_mt(float *params, float *momentum, uint32_t N, uint64_t P,
-                        const wash_ref_segment *segs, uint32_t nsegs,
-                        uint64_t seed, uint64_t step, uint64_t *selected_count,
-                        uint32_t nthreads)
+static int shuffle_mt(int gap_stream, float *params, float *momentum, uint32_t N, uint64_t P,
+                      const wash_ref_segment *segs, uint32_t nsegs,
+                      uint64_t seed, uint64_t step, uint64_t *selected_count,
+                      uint32_t nthreads)
 {
     if (nthreads == 0) return -1;
     if (nthreads > 256) nthreads = 256;
@@ -298,8 +500,11 @@ int wash_shuffle_ref_mt(float *params, float *momentum, uint32_t N, uint64_t P,
     for (uint32_t k = 0; k < nthreads; ++k) {
         shuffle_job *j = &jobs[k];
         j->params = params; j->momentum = momentum; j->N = N; j->P = P;
-        j->g_begin = (uint64_t)(((__uint128_t)P * k) / nthreads);
-        j->g_end = (uint64_t)(((__uint128_t)P * (k + 1u)) / nthreads);
+        /* cuts on multiples of 1024 (the piece grid of the gap stream; harmless for v1) */
+        j->g_begin = (uint64_t)(((__uint128_t)P * k) / nthreads) / WASH_REF_PIECE * WASH_REF_PIECE;
+        j->g_end = (uint64_t)(((__uint128_t)P * (k + 1u)) / nthreads) / WASH_REF_PIECE * WASH_REF_PIECE;
+        if (k + 1u == nthreads) j->g_end = P;
+        j->gap_stream = gap_stream;
         j->segs = segs; j->nsegs = nsegs; j->seed = seed; j->step = step;
         j->count = 0; j->status = 0;
     }
@@ -317,4 +522,20 @@ int wash_shuffle_ref_mt(float *params, float *momentum, uint32_t N, uint64_t P,
     }
     if (status == 0 && selected_count != NULL) *selected_count += count;
     return status;
+}
+
+int wash_shuffle_ref_mt(float *params, float *momentum, uint32_t N, uint64_t P,
+                        const wash_ref_segment *segs, uint32_t nsegs,
+                        uint64_t seed, uint64_t step, uint64_t *selected_count,
+                        uint32_t nthreads)
+{
+    return shuffle_mt(0, params, momentum, N, P, segs, nsegs, seed, step, selected_count, nthreads);
+}
+
+int wash_shuffle_gap_ref_mt(float *params, float *momentum, uint32_t N, uint64_t P,
+                            const wash_ref_segment *segs, uint32_t nsegs,
+                            uint64_t seed, uint64_t step, uint64_t *selected_count,
+                            uint32_t nthreads)
+{
+    return shuffle_mt(1, params, momentum, N, P, segs, nsegs, seed, step, selected_count, nthreads);
 }
