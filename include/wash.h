@@ -99,6 +99,25 @@ int wash_shuffle(float *params, float *momentum, uint32_t N, uint64_t P,
                  uint64_t *selected_count, void *stream);
 
 /*
+ * The same shuffling step (Eq. 3, same law, same arguments, same errors) on a
+ * second random stream, "gap": instead of one Bernoulli draw per coordinate the
+ * distances between successive selected coordinates are drawn (geometric, by
+ * inversion: 1 + floor(log2(u) / log2(1-p)); the walk restarts at every
+ * multiple of 1024 coordinates and at every segment start, which keeps the
+ * trials independent because the geometric law has no memory).  The random-number
+ * work is then proportional to the number of SELECTED coordinates, p * P per
+ * step, the quantity the paper counts as communication volume (Sec. 3), instead
+ * of P.  The permutation of a selected coordinate is the one of wash_shuffle.
+ * Results differ bit for bit from wash_shuffle (different mask), are the same
+ * in law, and are a pure function of (seed, step, N, and the segment list after
+ * dropping empty segments and merging touching neighbours of equal p).
+ */
+int wash_shuffle_gap(float *params, float *momentum, uint32_t N, uint64_t P,
+                     const wash_segment *segs, uint32_t nsegs,
+                     uint64_t seed, uint64_t step,
+                     uint64_t *selected_count, void *stream);
+
+/*
  * Uniform average, Alg. 1 output line: out[g] = (1/N) sum_n params[n][g],
  * summed in fp64 in ascending n and rounded once to fp32.
  *   params  device, [N, P] fp32 (read only)      out  device, [P] fp32, must not overlap params

@@ -35,6 +35,8 @@ def _load():
     u32, u64, vp = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_void_p
     L.wash_shuffle.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp, vp]
     L.wash_shuffle.restype = ctypes.c_int
+    L.wash_shuffle_gap.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp, vp]
+    L.wash_shuffle_gap.restype = ctypes.c_int
     L.wash_average.argtypes = [vp, vp, u32, u64, vp]
     L.wash_average.restype = ctypes.c_int
     L.papa_ema.argtypes = [vp, u32, u64, ctypes.c_float, vp]
@@ -92,6 +94,16 @@ class SegmentList:
 def wash_shuffle(params: torch.Tensor, momentum: Optional[torch.Tensor], segs, seed: int, step: int,
                  selected_count: Optional[torch.Tensor] = None) -> None:
     """In-place shuffling step (Eq. 3) on a device population; see wash.h."""
+    _shuffle(_lib.wash_shuffle, "wash_shuffle", params, momentum, segs, seed, step, selected_count)
+
+
+def wash_shuffle_gap(params: torch.Tensor, momentum: Optional[torch.Tensor], segs, seed: int, step: int,
+                     selected_count: Optional[torch.Tensor] = None) -> None:
+    """The same step on the gap-sampled mask stream (work proportional to p*P); see wash.h."""
+    _shuffle(_lib.wash_shuffle_gap, "wash_shuffle_gap", params, momentum, segs, seed, step, selected_count)
+
+
+def _shuffle(fn, name, params, momentum, segs, seed, step, selected_count) -> None:
     N, P = _dev_pop(params, "params")
     mom_ptr = None
     if momentum is not None:
@@ -107,9 +119,8 @@ def wash_shuffle(params: torch.Tensor, momentum: Optional[torch.Tensor], segs, s
     if not isinstance(segs, SegmentList):
         segs = SegmentList(segs)
     with torch.cuda.device(params.device):
-        rc = _lib.wash_shuffle(params.data_ptr(), mom_ptr, N, P, segs.ptr, segs.n, seed, step, cnt_ptr,
-                               _stream(params))
-    _check(rc, "wash_shuffle")
+        rc = fn(params.data_ptr(), mom_ptr, N, P, segs.ptr, segs.n, seed, step, cnt_ptr, _stream(params))
+    _check(rc, name)
 
 
 def wash_average(params: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:

@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "../../include/wash.h"
+#include "gaplog.hpp"
 #include "kernels.hpp"
 
 namespace {
@@ -48,10 +49,11 @@ struct TableKey {
     int device;
     uint64_t P;
     uint32_t tile_coords;
+    int gap;                    // 1: segment params are gap-stream scales, 0: stream-v1 thresholds
     std::vector<wash::DevSegment> segs;
     bool operator==(const TableKey &o) const
     {
-        return device == o.device && P == o.P && tile_coords == o.tile_coords && segs.size() == o.segs.size() &&
+        return device == o.device && P == o.P && tile_coords == o.tile_coords && gap == o.gap && segs.size() == o.segs.size() &&
                (segs.empty() || std::memcmp(segs.data(), o.segs.data(), segs.size() * sizeof(wash::DevSegment)) == 0);
     }
 };
@@ -78,10 +80,10 @@ uint32_t choose_tile_coords(uint64_t P)
 }
 
 // Builds (or finds) the device table for this call; on success *out points at the cached entry.
-int get_table(int device, uint64_t P, uint32_t tile_coords, std::vector<wash::DevSegment> &&active,
+int get_table(int device, uint64_t P, uint32_t tile_coords, bool gap, std::vector<wash::DevSegment> &&active,
               const Table **out)
 {
-    TableKey key{device, P, tile_coords, std::move(active)};
+    TableKey key{device, P, tile_coords, gap ? 1 : 0, std::move(active)};
     for (auto it = g_tables.begin(); it != g_tables.end(); ++it) {
         if (it->key == key) {
             g_tables.splice(g_tables.begin(), g_tables, it);
@@ -151,8 +153,9 @@ int check_population(const void *params, uint32_t N, uint64_t P)
 
 extern "C" {
 
-int wash_shuffle(float *params, float *momentum, uint32_t N, uint64_t P, const wash_segment *segs,
-                 uint32_t nsegs, uint64_t seed, uint64_t step, uint64_t *selected_count, void *stream)
+static int shuffle_common(bool gap, float *params, float *momentum, uint32_t N, uint64_t P,
+                          const wash_segment *segs, uint32_t nsegs, uint64_t seed, uint64_t step,
+                          uint64_t *selected_count, void *stream)
 {
     g_detail[0] = 0;
     if (int rc = check_population(params, N, P)) return rc;
@@ -178,14 +181,41 @@ int wash_shuffle(float *params, float *momentum, uint32_t N, uint64_t P, const w
         if (sg.offset < prev_end)
             return fail(WASH_EINVAL, "segment %u: unsorted or overlapping", s);
         prev_end = sg.offset + sg.length;
+        if (sg.length == 0) continue;
+        if (gap) {
+            // touching neighbours with the same p are one segment of the stream; the param slot holds p until
+            // the merge is done (p = 0 segments take part in the merge and are dropped afterwards)
+            uint64_t pbits;
+            const double pval = (sg.p == 0.0) ? 0.0 : sg.p;   // -0.0 and 0.0 are the same probability
+            std::memcpy(&pbits, &pval, sizeof(pbits));
+            wash::DevSegment d{sg.offset, sg.offset + sg.length, pbits};
+            if (!active.empty() && active.back().end == d.begin && active.back().param == d.param)
+                active.back().end = d.end;
+            else
+                active.push_back(d);
+            continue;
+        }
         const uint64_t T = threshold_of(sg.p);
-        if (T == 0 || sg.length == 0) continue;     // never selected: not scanned at all
-        wash::DevSegment d{sg.offset, sg.offset + sg.length, static_cast<uint32_t>(T - 1u), 0u};
+        if (T == 0) continue;                       // never selected: not scanned at all
+        wash::DevSegment d{sg.offset, sg.offset + sg.length, T - 1u};
         // neighbours with the same threshold behave as one segment
-        if (!active.empty() && active.back().end == d.begin && active.back().thr_m1 == d.thr_m1)
+        if (!active.empty() && active.back().end == d.begin && active.back().param == d.param)
             active.back().end = d.end;
         else
             active.push_back(d);
+    }
+    if (gap) {
+        size_t kept = 0;
+        for (const wash::DevSegment &d : active) {
+            double pval;
+            std::memcpy(&pval, &d.param, sizeof(pval));
+            if (pval == 0.0) continue;
+            const double scale = wash::gap_scale(pval);
+            wash::DevSegment out = d;
+            std::memcpy(&out.param, &scale, sizeof(scale));
+            active[kept++] = out;
+        }
+        active.resize(kept);
     }
     if (active.empty()) return WASH_OK;
 
@@ -194,9 +224,9 @@ int wash_shuffle(float *params, float *momentum, uint32_t N, uint64_t P, const w
     if (e != hipSuccess) return fail_hip("hipGetDevice", e);
 
     std::lock_guard<std::mutex> lock(g_mutex);
-    const uint32_t tile_coords = choose_tile_coords(P);
+    const uint32_t tile_coords = gap ? wash::kGapPiece : choose_tile_coords(P);
     const Table *table = nullptr;
-    if (int rc = get_table(device, P, tile_coords, std::move(active), &table)) return rc;
+    if (int rc = get_table(device, P, tile_coords, gap, std::move(active), &table)) return rc;
 
     wash::ShuffleArgs a{};
     a.params = reinterpret_cast<uint32_t *>(params);
@@ -215,10 +245,31 @@ int wash_shuffle(float *params, float *momentum, uint32_t N, uint64_t P, const w
     a.step = static_cast<uint32_t>(step);
     a.selected_count = reinterpret_cast<unsigned long long *>(selected_count);
     a.count_slots = selected_count ? reinterpret_cast<unsigned long long *>(base) : nullptr;
-    e = wash::launch_shuffle(a, static_cast<hipStream_t>(stream));
-    if (e != hipSuccess) return fail_hip("wash_shuffle launch", e);
+    if (gap) {
+        // a wavefront walks up to 64 restart blocks; fewer when that would leave the chip short of wavefronts
+        uint32_t bpw = 64;
+        while (bpw > 1 && a.num_tiles / bpw < 4096) bpw >>= 1;
+        a.blocks_per_wave = bpw;
+        e = wash::launch_shuffle_gap(a, static_cast<hipStream_t>(stream));
+    } else {
+        e = wash::launch_shuffle(a, static_cast<hipStream_t>(stream));
+    }
+    if (e != hipSuccess) return fail_hip("shuffle launch", e);
     return WASH_OK;
 }
+
+int wash_shuffle(float *params, float *momentum, uint32_t N, uint64_t P, const wash_segment *segs,
+                 uint32_t nsegs, uint64_t seed, uint64_t step, uint64_t *selected_count, void *stream)
+{
+    return shuffle_common(false, params, momentum, N, P, segs, nsegs, seed, step, selected_count, stream);
+}
+
+int wash_shuffle_gap(float *params, float *momentum, uint32_t N, uint64_t P, const wash_segment *segs,
+                     uint32_t nsegs, uint64_t seed, uint64_t step, uint64_t *selected_count, void *stream)
+{
+    return shuffle_common(true, params, momentum, N, P, segs, nsegs, seed, step, selected_count, stream);
+}
+
 
 int wash_average(const float *params, float *out, uint32_t N, uint64_t P, void *stream)
 {

@@ -9,8 +9,8 @@ namespace wash {
 struct DevSegment {
     uint64_t begin;     // first coordinate
     uint64_t end;       // one past the last coordinate
-    uint32_t thr_m1;    // coordinate selected  <=>  mask word <= thr_m1   (= round(p*2^32) - 1)
-    uint32_t pad;
+    uint64_t param;     // stream v1: low 32 bits = round(p*2^32) - 1 (selected <=> mask word <= it)
+                        // gap stream: bit pattern of the double 1/log2(1-p) (0.0 for p = 1)
 };
 
 constexpr uint32_t kNoSegment = 0xFFFFFFFFu;
@@ -24,7 +24,9 @@ struct ShuffleArgs {
     uint32_t nsegs;
     const uint32_t *tile_first; // per tile: first active segment ending after the tile start, or kNoSegment
     uint64_t num_tiles;
-    uint32_t tile_coords;       // coordinates per tile (one wavefront scans one tile), multiple of 256
+    uint32_t tile_coords;       // stream v1: coordinates per tile (one wavefront scans one tile), multiple of 256
+                                // gap stream: 1024 (a tile is one restart block; a wavefront walks `blocks_per_wave` of them)
+    uint32_t blocks_per_wave;   // gap stream only: 1 .. 64
     uint32_t key_lo, key_hi;    // seed
     uint32_t step;
     unsigned long long *selected_count; // caller's counter, or nullptr
@@ -37,6 +39,7 @@ constexpr uint32_t kCountSlotStride = 16;   // in 8-byte words
 constexpr size_t kCountSlotBytes = static_cast<size_t>(kCountSlots) * kCountSlotStride * 8;
 
 hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream);
+hipError_t launch_shuffle_gap(const ShuffleArgs &a, hipStream_t stream);
 hipError_t launch_average(const float *params, float *out, uint32_t N, uint64_t P, hipStream_t stream);
 hipError_t launch_copy(const float *src, float *dst, uint64_t n, hipStream_t stream);
 hipError_t launch_ema(float *params, uint32_t N, uint64_t P, float alpha, bool nontemporal, hipStream_t stream);

@@ -17,6 +17,7 @@
 //            final after step i its value is stored to row i right there.
 // Everything random is integer arithmetic, so the result is bit-identical to
 // any other implementation of the same stream.
+#include "gaplog.hpp"
 #include "kernels.hpp"
 #include "philox.hpp"
 
@@ -142,7 +143,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
         bool sel[4];
         if (uniform) {
 #pragma unroll
-            for (int k = 0; k < 4; ++k) sel[k] = (w[k] <= seg0.thr_m1) && (g0 + k < tile_end);
+            for (int k = 0; k < 4; ++k) sel[k] = (w[k] <= static_cast<uint32_t>(seg0.param)) && (g0 + k < tile_end);
         } else {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -152,7 +153,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
                 bool s = false;
                 if (walk < a.nsegs && g < tile_end) {
                     const DevSegment sg = a.segs[walk];
-                    s = (sg.begin <= g) && (w[k] <= sg.thr_m1);
+                    s = (sg.begin <= g) && (w[k] <= static_cast<uint32_t>(sg.param));
                 }
                 sel[k] = s;
             }
@@ -206,6 +207,116 @@ __global__ __launch_bounds__(kCountSlots) void fold_count_kernel(unsigned long l
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Gap stream: the mask is walked, not scanned.  A lane owns one restart block of 1024
+// coordinates and draws the distances between selected coordinates (geometric by inversion), so
+// the random-number work follows p*P instead of P.  A wavefront walks `blocks_per_wave`
+// neighbouring blocks in lock step; every lane parks its finds in a short private list, and when
+// a list fills up (or every lane is done) the lists are poured, lane after lane, into the queue:
+// that keeps the queue in ascending coordinate order, so the permute batches touch neighbouring
+// cache lines exactly as in the scanning kernel.
+
+constexpr int kListCap = 16;                 // finds a lane can park between two flushes
+constexpr int kGapQueueCap = kWave * kListCap;
+
+template <bool kMomentum>
+__global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_gap_kernel(const ShuffleArgs a)
+{
+    extern __shared__ uint32_t lds[];
+    const uint32_t lane = lane_id();
+    const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const uint32_t waves_per_block = blockDim.x / kWave;
+    const uint64_t wave = static_cast<uint64_t>(blockIdx.x) * waves_per_block + wave_in_block;
+    const uint32_t bpw = a.blocks_per_wave;
+    const uint64_t first_block = wave * bpw;
+    if (first_block >= a.num_tiles) return;
+
+    const uint32_t slab_words = a.N * kWave;
+    const uint32_t per_wave = kGapQueueCap + kWave * kListCap / 2 + slab_words * (kMomentum ? 2u : 1u);
+    uint32_t *queue = lds + wave_in_block * per_wave;
+    uint16_t *list = reinterpret_cast<uint16_t *>(queue + kGapQueueCap) + lane * kListCap;
+    uint32_t *slab = queue + kGapQueueCap + kWave * kListCap / 2;
+    uint32_t *slab_m = slab + slab_words;
+    const uint64_t tile_begin = first_block * kGapPiece;
+
+    // lane state: the piece [piece_off .. end_off) of its block it is walking, as offsets in the block
+    const uint64_t blk = first_block + lane;
+    const uint64_t blk_begin = blk * kGapPiece;
+    const uint64_t blk_end = min(blk_begin + kGapPiece, a.P);
+    bool active = false;
+    uint32_t seg = kNoSegment, piece_off = 0, end_off = 0, next_off = 0, draw = 0;
+    double scale = 0.0;
+    if (lane < bpw && blk < a.num_tiles) {
+        seg = a.tile_first[blk];
+        active = seg != kNoSegment;
+    }
+    if (active) {
+        const DevSegment sg = a.segs[seg];
+        piece_off = static_cast<uint32_t>(max(sg.begin, blk_begin) - blk_begin);
+        end_off = static_cast<uint32_t>(min(sg.end, blk_end) - blk_begin);
+        scale = __longlong_as_double(static_cast<long long>(sg.param));
+        next_off = piece_off;
+    }
+
+    uint32_t parked = 0;       // finds in this lane's list
+    uint32_t selected = 0;     // wave-uniform, total of the wave
+    Words4 r{0, 0, 0, 0};
+    while (__ballot(active) != 0) {
+        if (active) {
+            if ((draw & 1u) == 0) {
+                const uint64_t s = blk_begin + piece_off;
+                r = philox4x32_10(static_cast<uint32_t>(s), static_cast<uint32_t>(s >> 32), a.step,
+                                  0x80000000u + (draw >> 1), a.key_lo, a.key_hi);
+            }
+            const uint32_t hi = (draw & 1u) ? r.w2 : r.w0, lo = (draw & 1u) ? r.w3 : r.w1;
+            const uint64_t U = ((static_cast<uint64_t>(hi) << 32) | lo) >> 11;
+            const uint32_t found = next_off + gap_distance(U, scale) - 1u;
+            if (found < end_off) {
+                list[parked++] = static_cast<uint16_t>(found);
+                next_off = found + 1u;
+                ++draw;
+            } else {
+                // this piece is finished: the next segment may start inside the same block
+                ++seg;
+                active = false;
+                if (seg < a.nsegs) {
+                    const DevSegment sg = a.segs[seg];
+                    if (sg.begin < blk_end) {
+                        piece_off = static_cast<uint32_t>(sg.begin - blk_begin);
+                        end_off = static_cast<uint32_t>(min(sg.end, blk_end) - blk_begin);
+                        scale = __longlong_as_double(static_cast<long long>(sg.param));
+                        next_off = piece_off;
+                        draw = 0;
+                        active = true;
+                    }
+                }
+            }
+        }
+        // pour the lists into the queue when one is full or everybody is done
+        if (__ballot(parked == kListCap) == 0 && __ballot(active) != 0) continue;
+        uint32_t before = parked;                    // exclusive prefix of `parked` over the lanes
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const uint32_t up = __shfl_up(before, off, kWave);
+            if (lane >= static_cast<uint32_t>(off)) before += up;
+        }
+        const uint32_t total = __shfl(before, kWave - 1, kWave);
+        before -= parked;
+        for (uint32_t j = 0; j < parked; ++j) queue[before + j] = lane * kGapPiece + list[j];
+        parked = 0;
+        wave_lds_sync();
+        for (uint32_t done = 0; done < total; done += kWave) {
+            permute_batch<kMomentum>(a, tile_begin, queue + done, min(total - done, static_cast<uint32_t>(kWave)),
+                                     slab, slab_m);
+        }
+        selected += total;
+        wave_lds_sync();
+    }
+    if (a.count_slots != nullptr && selected != 0 && lane == 0)
+        atomicAdd(a.count_slots + (wave % kCountSlots) * kCountSlotStride, static_cast<unsigned long long>(selected));
+}
+
 }  // namespace
 
 hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream)
@@ -224,6 +335,30 @@ hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream)
         hipLaunchKernelGGL(shuffle_kernel<true>, grid, block, lds_bytes, stream, a);
     else
         hipLaunchKernelGGL(shuffle_kernel<false>, grid, block, lds_bytes, stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || a.count_slots == nullptr) return e;
+    hipLaunchKernelGGL(fold_count_kernel, dim3(1), dim3(kCountSlots), 0, stream, a.count_slots, a.selected_count);
+    return hipGetLastError();
+}
+
+hipError_t launch_shuffle_gap(const ShuffleArgs &a, hipStream_t stream)
+{
+    if (a.num_tiles == 0 || a.nsegs == 0) return hipSuccess;
+    if (a.blocks_per_wave == 0 || a.blocks_per_wave > kWave || a.tile_coords != kGapPiece)
+        return hipErrorInvalidValue;
+    const size_t per_wave = (kGapQueueCap + kWave * kListCap / 2 +
+                             static_cast<size_t>(a.N) * kWave * (a.momentum ? 2 : 1)) * sizeof(uint32_t);
+    uint32_t waves = kWavesPerBlock;
+    while (waves > 1 && per_wave * waves > 65536) waves >>= 1;
+    if (per_wave * waves > 65536) return hipErrorInvalidConfiguration;
+    const uint64_t nwaves = (a.num_tiles + a.blocks_per_wave - 1) / a.blocks_per_wave;
+    const uint64_t blocks64 = (nwaves + waves - 1) / waves;
+    if (blocks64 > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
+    const dim3 grid(static_cast<uint32_t>(blocks64)), block(kWave * waves);
+    if (a.momentum)
+        hipLaunchKernelGGL(shuffle_gap_kernel<true>, grid, block, per_wave * waves, stream, a);
+    else
+        hipLaunchKernelGGL(shuffle_gap_kernel<false>, grid, block, per_wave * waves, stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.count_slots == nullptr) return e;
     hipLaunchKernelGGL(fold_count_kernel, dim3(1), dim3(kCountSlots), 0, stream, a.count_slots, a.selected_count);

@@ -41,7 +41,8 @@ def _close(got, ref, pop_abs_mean):
     return bool(np.all(np.abs(got - ref) <= 1e-6 * scale))
 
 
-def _full_config(wash, index, steps, p_values=(None,), check_ema=True):
+def _full_config(wash, index, steps, p_values=(None,), check_ema=True, stream="v1"):
+    shuffle = wash.wash_shuffle if stream == "v1" else wash.wash_shuffle_gap
     cfg = get_config(index)
     pop, mom = device_population(cfg.tensors(), cfg.N, cfg.init, cfg.data_seed, cfg.momentum)
     ref = pop.cpu().numpy()
@@ -52,9 +53,9 @@ def _full_config(wash, index, steps, p_values=(None,), check_ema=True):
         segs_list = cfg.segments(p)
         segs = wash.SegmentList(segs_list)
         for _ in range(steps):
-            print(f"config {index} p={p} step {step}", flush=True)
-            wash.wash_shuffle(pop, mom, segs, cfg.seed, step, cnt)
-            ref_cnt += oracle.shuffle(ref, refm, segs_list, cfg.seed, step, threads=THREADS)
+            print(f"config {index} p={p} step {step} stream {stream}", flush=True)
+            shuffle(pop, mom, segs, cfg.seed, step, cnt)
+            ref_cnt += oracle.shuffle(ref, refm, segs_list, cfg.seed, step, threads=THREADS, stream=stream)
             step += 1
     torch.cuda.synchronize()
     assert int(cnt.item()) == ref_cnt and ref_cnt > 0
@@ -73,24 +74,33 @@ def _full_config(wash, index, steps, p_values=(None,), check_ema=True):
         assert _close(pop.cpu().numpy(), ref, abs_mean[None, :]), "EMA outside 1e-6"
 
 
-def test_config1_flat(wash):
-    _full_config(wash, 1, steps=1)
+STREAMS = ["v1", "gap"]
 
 
-def test_config2_resnet18_100_steps(wash):
-    _full_config(wash, 2, steps=100)
+@pytest.mark.parametrize("stream", STREAMS)
+def test_config1_flat(wash, stream):
+    _full_config(wash, 1, steps=1, stream=stream)
 
 
-def test_config3_resnet50_momentum_100_steps(wash):
-    _full_config(wash, 3, steps=100)
+@pytest.mark.parametrize("stream", STREAMS)
+def test_config2_resnet18_100_steps(wash, stream):
+    _full_config(wash, 2, steps=100, stream=stream, check_ema=(stream == "v1"))
 
 
-def test_config4_vit_p_sweep(wash):
+@pytest.mark.parametrize("stream", STREAMS)
+def test_config3_resnet50_momentum_100_steps(wash, stream):
+    _full_config(wash, 3, steps=100, stream=stream, check_ema=(stream == "v1"))
+
+
+@pytest.mark.parametrize("stream", STREAMS)
+def test_config4_vit_p_sweep(wash, stream):
     cfg = get_config(4)
-    _full_config(wash, 4, steps=2, p_values=cfg.p_sweep)
+    _full_config(wash, 4, steps=2, p_values=cfg.p_sweep, stream=stream, check_ema=(stream == "v1"))
 
 
-def test_config5_stress_windows_and_invariants(wash):
+@pytest.mark.parametrize("stream", STREAMS)
+def test_config5_stress_windows_and_invariants(wash, stream):
+    shuffle = wash.wash_shuffle if stream == "v1" else wash.wash_shuffle_gap
     cfg = get_config(5)
     N, P = cfg.N, cfg.P
     segs_list = cfg.segments()
@@ -115,12 +125,15 @@ def test_config5_stress_windows_and_invariants(wash):
     seg_len = segs_list[0][1]
     starts = [0, P - W, seg_len - W // 2, 57 * seg_len - 12345, 199 * seg_len - W + 7, 4096 * 1000 - 3,
               (P // 2 // 4096) * 4096 - W // 2, 123_456_789]
-    init = [(pop[:, g0:g0 + W].clone(), mom[:, g0:g0 + W].clone()) for g0 in starts]
+    if stream == "gap":          # the oracle walks whole 1024-blocks: windows sit on that grid
+        starts = sorted({g0 // 1024 * 1024 for g0 in starts})
+    widths = [min(W, P - g0) if g0 + W + 1024 < P else P - g0 for g0 in starts]
+    init = [(pop[:, g0:g0 + w].clone(), mom[:, g0:g0 + w].clone()) for g0, w in zip(starts, widths)]
 
     cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
     steps = cfg.steps
     for step in range(steps):
-        wash.wash_shuffle(pop, mom, segs, cfg.seed, step, cnt)
+        shuffle(pop, mom, segs, cfg.seed, step, cnt)
     torch.cuda.synchronize()
     print("config 5 shuffled", flush=True)
 
@@ -137,15 +150,15 @@ def test_config5_stress_windows_and_invariants(wash):
     assert abs(int(cnt.item()) - mean) < 6 * math.sqrt(var)
 
     avg = wash.wash_average(pop)
-    for g0, (ip, im) in zip(starts, init):
-        print(f"config 5 window at {g0}", flush=True)
+    for g0, w, (ip, im) in zip(starts, widths, init):
+        print(f"config 5 window at {g0} width {w}", flush=True)
         ref, refm = ip.cpu().numpy(), im.cpu().numpy()
         for step in range(steps):
-            oracle.shuffle_window(ref, refm, P, g0, segs_list, cfg.seed, step)
-        got = pop[:, g0:g0 + W].contiguous().cpu().numpy()
-        gotm = mom[:, g0:g0 + W].contiguous().cpu().numpy()
+            oracle.shuffle_window(ref, refm, P, g0, segs_list, cfg.seed, step, stream=stream)
+        got = pop[:, g0:g0 + w].contiguous().cpu().numpy()
+        gotm = mom[:, g0:g0 + w].contiguous().cpu().numpy()
         assert np.array_equal(_bits(got), _bits(ref)), f"params window {g0}"
         assert np.array_equal(_bits(gotm), _bits(refm)), f"momentum window {g0}"
         assert not np.array_equal(_bits(got), _bits(ip.cpu().numpy()))
         ref_avg = oracle.average(ref)
-        assert _close(avg[g0:g0 + W].cpu().numpy(), ref_avg, np.abs(ref).mean(axis=0)), f"average window {g0}"
+        assert _close(avg[g0:g0 + w].cpu().numpy(), ref_avg, np.abs(ref).mean(axis=0)), f"average window {g0}"

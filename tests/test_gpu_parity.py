@@ -38,12 +38,19 @@ def _ragged_segments(P, ps):
     return segs
 
 
-def _run_shuffle(wash, pop, mom, segs, seed, step, tile=0):
+STREAMS = ["v1", "gap"]
+
+
+def _fn(wash, stream):
+    return wash.wash_shuffle if stream == "v1" else wash.wash_shuffle_gap
+
+
+def _run_shuffle(wash, pop, mom, segs, seed, step, tile=0, stream="v1"):
     wash.wash_set_option(wash.OPT_TILE_COORDS, tile)
     d = torch.from_numpy(pop).cuda()
     dm = torch.from_numpy(mom).cuda() if mom is not None else None
     cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
-    wash.wash_shuffle(d, dm, segs, seed, step, cnt)
+    _fn(wash, stream)(d, dm, segs, seed, step, cnt)
     torch.cuda.synchronize()
     return d.cpu().numpy(), (dm.cpu().numpy() if dm is not None else None), int(cnt.item())
 
@@ -52,35 +59,37 @@ SHAPES = [(1, 1), (1, 77), (2, 3), (2, 255), (3, 256), (4, 257), (5, 4097), (8, 
           (20, 33333), (31, 5000), (32, 20011)]
 
 
+@pytest.mark.parametrize("stream", STREAMS)
 @pytest.mark.parametrize("N,P", SHAPES)
 @pytest.mark.parametrize("p", [0.0, 0.001, 0.05, 0.5, 1.0])
-def test_shuffle_one_segment(wash, N, P, p):
-    print(f"case N={N} P={P} p={p}", flush=True)
+def test_shuffle_one_segment(wash, N, P, p, stream):
+    print(f"case N={N} P={P} p={p} stream={stream}", flush=True)
     pop = distinct_population(N, P)
     segs = [(0, P, p)]
     ref = pop.copy()
-    ref_cnt = oracle.shuffle(ref, None, segs, 17, 4)
-    got, _, cnt = _run_shuffle(wash, pop, None, segs, 17, 4)
+    ref_cnt = oracle.shuffle(ref, None, segs, 17, 4, stream=stream)
+    got, _, cnt = _run_shuffle(wash, pop, None, segs, 17, 4, stream=stream)
     assert cnt == ref_cnt
     assert np.array_equal(_bits(got), _bits(ref))
 
 
-@pytest.mark.parametrize("N,P", [(2, 1000), (5, 40001), (10, 123457), (20, 65539), (32, 9001)])
-@pytest.mark.parametrize("tile", [0, 256, 4096, 65536])
-def test_shuffle_ragged_segments_momentum(wash, N, P, tile):
-    print(f"case N={N} P={P} tile={tile}", flush=True)
+@pytest.mark.parametrize("N,P", [(2, 1000), (5, 40001), (10, 123457), (20, 65539), (32, 9001), (8, 1_500_007)])
+@pytest.mark.parametrize("tile,stream", [(0, "v1"), (256, "v1"), (4096, "v1"), (65536, "v1"), (0, "gap")])
+def test_shuffle_ragged_segments_momentum(wash, N, P, tile, stream):
+    print(f"case N={N} P={P} tile={tile} stream={stream}", flush=True)
     pop = distinct_population(N, P)
     mom = distinct_population(N, P, base=0x40000000)
     segs = _ragged_segments(P, [0.3, 0.0, 1.0, 0.01, 0.3, 0.3, 0.002, 0.9, 0.05])
     ref, refm = pop.copy(), mom.copy()
-    ref_cnt = oracle.shuffle(ref, refm, segs, 0xABCDEF0123456789, 4294967295)
-    got, gotm, cnt = _run_shuffle(wash, pop, mom, segs, 0xABCDEF0123456789, 4294967295, tile)
+    ref_cnt = oracle.shuffle(ref, refm, segs, 0xABCDEF0123456789, 4294967295, stream=stream)
+    got, gotm, cnt = _run_shuffle(wash, pop, mom, segs, 0xABCDEF0123456789, 4294967295, tile, stream)
     assert cnt == ref_cnt
     assert np.array_equal(_bits(got), _bits(ref))
     assert np.array_equal(_bits(gotm), _bits(refm))
 
 
-def test_shuffle_many_tiny_segments(wash):
+@pytest.mark.parametrize("stream", STREAMS)
+def test_shuffle_many_tiny_segments(wash, stream):
     # tensors of 1..70 elements back to back, probabilities cycling, some zero
     N, P = 6, 50000
     rng = np.random.default_rng(0)
@@ -92,13 +101,14 @@ def test_shuffle_many_tiny_segments(wash):
         k += 1
     pop = distinct_population(N, P)
     ref = pop.copy()
-    ref_cnt = oracle.shuffle(ref, None, segs, 5, 6)
+    ref_cnt = oracle.shuffle(ref, None, segs, 5, 6, stream=stream)
     for tile in (256, 1024, 0):
-        got, _, cnt = _run_shuffle(wash, pop, None, segs, 5, 6, tile)
+        got, _, cnt = _run_shuffle(wash, pop, None, segs, 5, 6, tile, stream)
         assert cnt == ref_cnt and np.array_equal(_bits(got), _bits(ref))
 
 
-def test_shuffle_consecutive_steps_and_special_values(wash):
+@pytest.mark.parametrize("stream", STREAMS)
+def test_shuffle_consecutive_steps_and_special_values(wash, stream):
     N, P = 7, 30011
     bits = np.random.default_rng(1).integers(0, 2 ** 32, size=(N, P), dtype=np.uint64).astype(np.uint32)
     bits[:, :3] = np.array([0x7FC00001, 0xFFC12345, 0x80000000], dtype=np.uint32)   # NaN payloads, -0.0
@@ -107,10 +117,22 @@ def test_shuffle_consecutive_steps_and_special_values(wash):
     ref = pop.copy()
     d = torch.from_numpy(pop).cuda()
     for step in range(12):
-        oracle.shuffle(ref, None, segs, 3, step)
-        wash.wash_shuffle(d, None, segs, 3, step)
+        oracle.shuffle(ref, None, segs, 3, step, stream=stream)
+        _fn(wash, stream)(d, None, segs, 3, step)
     torch.cuda.synchronize()
     assert np.array_equal(_bits(d.cpu().numpy()), _bits(ref))
+
+
+def test_gap_equal_p_neighbours_merge_and_p1_matches_v1(wash):
+    N, P = 5, 70_003
+    pop = distinct_population(N, P)
+    one = _run_shuffle(wash, pop, None, [(0, P, 0.04)], 9, 1, stream="gap")
+    cut = _run_shuffle(wash, pop, None, [(0, 777, 0.04), (777, 0, 0.9), (777, 3000, 0.04), (3777, P - 3777, 0.04)],
+                       9, 1, stream="gap")
+    assert one[2] == cut[2] and np.array_equal(_bits(one[0]), _bits(cut[0]))
+    a = _run_shuffle(wash, pop, None, [(0, P, 1.0)], 9, 1, stream="gap")
+    b = _run_shuffle(wash, pop, None, [(0, P, 1.0)], 9, 1, stream="v1")
+    assert a[2] == b[2] == P and np.array_equal(_bits(a[0]), _bits(b[0]))
 
 
 def test_shuffle_is_deterministic_and_tile_independent(wash):
