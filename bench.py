@@ -68,7 +68,7 @@ def kernel_rooflines(N, P, bufs, frac_selected, t_ms):
     return out
 
 
-def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True):
+def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, stream="v1"):
     """Time the hot path on one workload. Returns a dict of measurements."""
     from workloads import device_population
 
@@ -87,8 +87,10 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True):
 
     step_no = [0]
 
+    shuffle_fn = wash.wash_shuffle if stream == "v1" else wash.wash_shuffle_gap
+
     def do_shuffle():
-        wash.wash_shuffle(pop, mom, segs, cfg.seed, step_no[0], cnt if count else None)
+        shuffle_fn(pop, mom, segs, cfg.seed, step_no[0], cnt if count else None)
         step_no[0] += 1
 
     def do_ema():
@@ -124,12 +126,13 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True):
     selected = int(cnt.item()) / steps
     frac_sel = _expected_fraction(segs_list, P)
     res = {
-        "config": cfg.index, "name": cfg.name, "N": N, "P": P, "segments": len(segs_list),
+        "config": cfg.index, "name": cfg.name, "stream": stream, "N": N, "P": P, "segments": len(segs_list),
         "momentum": bool(cfg.momentum), "expected_fraction": frac_sel,
         "selected_per_step": selected, "steps": steps,
         "ms_per_step": total_ms / steps, "wall_ms_per_step": wall * 1e3 / steps,
         "avg_us": {k: v * 1e3 for k, v in avg_ms.items()},
         "median_us": {k: v * 1e3 for k, v in med_ms.items()},
+        "first_steps_us": {k: [round(x * 1e3, 1) for x in tm.ms(k)[:12]] for k in avg_ms},
         "shuffle_coords_per_s": P / (avg_ms["wash_shuffle"] * 1e-3),
         "pass_coords_per_s": P / (total_ms / steps * 1e-3),
         "population_bytes": N * P * 4 * bufs,
@@ -214,10 +217,13 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="1..5 (default 2: ResNet-18, N=5, p=0.001)")
     ap.add_argument("--p", type=float, default=None, help="override the shuffle probability of every tensor")
     ap.add_argument("--all-configs", action="store_true", help="also time the other configs (adds 'all_configs')")
+    ap.add_argument("--stream", choices=["v1", "gap"], default="v1",
+                    help="mask stream of the shuffle: v1 = wash_shuffle, gap = wash_shuffle_gap")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-count", action="store_true", help="do not ask wash_shuffle for the selected count")
     ap.add_argument("--stream-min-bytes", type=int, default=None,
                     help="override the population size from which average/EMA use non-temporal accesses")
+    ap.add_argument("--gap-blocks", type=int, default=None, help="override blocks per wavefront of the gap kernel")
     ap.add_argument("--tile-coords", type=int, default=None, help="override the shuffle tile size")
     ap.add_argument("--only", choices=["pass", "copy"], default="pass",
                     help="copy: run only the copy yardstick (for counter calibration)")
@@ -239,6 +245,8 @@ def main():
 
     if args.stream_min_bytes is not None:
         wash.wash_set_option(wash.OPT_STREAM_MIN_BYTES, args.stream_min_bytes)
+    if args.gap_blocks is not None:
+        wash.wash_set_option(wash.OPT_GAP_BLOCKS, args.gap_blocks)
     if args.tile_coords is not None:
         wash.wash_set_option(wash.OPT_TILE_COORDS, args.tile_coords)
 
@@ -247,7 +255,8 @@ def main():
         return
 
     cfg = get_config(args.config)
-    main_res = run_config(torch, wash, cfg, args.steps, args.warmup, p_override=args.p, count=not args.no_count)
+    main_res = run_config(torch, wash, cfg, args.steps, args.warmup, p_override=args.p, count=not args.no_count,
+                          stream=args.stream)
     yard = copy_yardstick(torch, wash)
 
     roof = main_res["roofline"]
@@ -272,6 +281,7 @@ def main():
         "shuffle_coords_per_s": main_res["shuffle_coords_per_s"],
         "selected_per_step": main_res["selected_per_step"],
         "kernel_us": main_res["avg_us"], "kernel_median_us": main_res["median_us"],
+        "kernel_first_steps_us": main_res["first_steps_us"],
         "roofline": roofline,
         "roofline_per_kernel": {k: {kk: vv for kk, vv in v.items()} | {"traffic": load_traffic(workload_key, k)}
                                 for k, v in roof.items()},
@@ -285,12 +295,13 @@ def main():
             for p in ps:
                 k = min(args.steps, c.steps if not c.p_sweep else 20)
                 k = max(k, 5)
-                res = run_config(torch, wash, c, k, min(args.warmup, 3), p_override=p)
-                res["p_override"] = p
-                rows.append(res)
-                print(f"[bench] config {c.index} p={p} done: shuffle {res['avg_us']['wash_shuffle']:.1f} us, "
-                      f"ema {res['avg_us']['papa_ema']:.1f} us, avg {res['avg_us']['wash_average']:.1f} us",
-                      file=sys.stderr, flush=True)
+                for st in ("v1", "gap"):
+                    res = run_config(torch, wash, c, k, min(args.warmup, 3), p_override=p, stream=st)
+                    res["p_override"] = p
+                    rows.append(res)
+                    print(f"[bench] config {c.index} p={p} stream {st} done: shuffle "
+                          f"{res['avg_us']['wash_shuffle']:.1f} us, ema {res['avg_us']['papa_ema']:.1f} us, "
+                          f"avg {res['avg_us']['wash_average']:.1f} us", file=sys.stderr, flush=True)
         line["all_configs"] = rows
 
     if not args.no_cpu_baseline:

@@ -169,8 +169,11 @@ const char *wash_last_error_detail(void);
  *   WASH_OPT_STREAM_MIN_BYTES  papa_ema uses non-temporal (cache-bypassing) accesses when the
  *                         population N*P*4 is at least this many bytes (default 256 MiB;
  *                         smaller populations are left to the 256 MB Infinity Cache)
+ *   WASH_OPT_GAP_BLOCKS   1024-coordinate blocks walked by one wavefront in wash_shuffle_gap;
+ *                         a power of two in [1, 64], or 0 = choose by P and p
  */
 #define WASH_OPT_TILE_COORDS 1
+#define WASH_OPT_GAP_BLOCKS 3
 #define WASH_OPT_STREAM_MIN_BYTES 2
 int wash_set_option(int option, int64_t value);
 

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libwash_hip.so")
 MAX_N = 32
 OPT_TILE_COORDS = 1
 OPT_STREAM_MIN_BYTES = 2
+OPT_GAP_BLOCKS = 3
 
 
 class WashError(RuntimeError):

@@ -68,6 +68,7 @@ std::mutex g_mutex;
 std::list<Table> g_tables;          // most recently used first
 constexpr size_t kMaxTables = 16;
 int64_t g_tile_coords_option = 0;   // 0 = choose by P
+int64_t g_gap_blocks_option = 0;    // 0 = choose by P
 int64_t g_stream_min_bytes = 256ll << 20;  // papa_ema on populations at least this large uses non-temporal accesses
 
 uint32_t choose_tile_coords(uint64_t P)
@@ -204,12 +205,14 @@ static int shuffle_common(bool gap, float *params, float *momentum, uint32_t N, 
         else
             active.push_back(d);
     }
+    double p_max = 0.0;
     if (gap) {
         size_t kept = 0;
         for (const wash::DevSegment &d : active) {
             double pval;
             std::memcpy(&pval, &d.param, sizeof(pval));
             if (pval == 0.0) continue;
+            if (pval > p_max) p_max = pval;
             const double scale = wash::gap_scale(pval);
             wash::DevSegment out = d;
             std::memcpy(&out.param, &scale, sizeof(scale));
@@ -246,9 +249,14 @@ static int shuffle_common(bool gap, float *params, float *momentum, uint32_t N, 
     a.selected_count = reinterpret_cast<unsigned long long *>(selected_count);
     a.count_slots = selected_count ? reinterpret_cast<unsigned long long *>(base) : nullptr;
     if (gap) {
-        // a wavefront walks up to 64 restart blocks; fewer when that would leave the chip short of wavefronts
+        // a wavefront walks up to 64 restart blocks; fewer when that would leave the 1024 SIMDs short of
+        // wavefronts (a wavefront's time is set by the longest walk and one memory round trip, not by its width)
         uint32_t bpw = 64;
-        while (bpw > 1 && a.num_tiles / bpw < 4096) bpw >>= 1;
+        while (bpw > 1 && a.num_tiles / bpw < 2048) bpw >>= 1;
+        // the 512 list slots of a wavefront are shared by its lanes: at high p fewer, longer lists keep the
+        // finds of one cache line in one batch (a lane's list should span several 32-coordinate lines)
+        while (bpw > 8 && static_cast<double>(bpw) * p_max > 0.5) bpw >>= 1;
+        if (g_gap_blocks_option != 0) bpw = static_cast<uint32_t>(g_gap_blocks_option);
         a.blocks_per_wave = bpw;
         e = wash::launch_shuffle_gap(a, static_cast<hipStream_t>(stream));
     } else {
@@ -345,6 +353,13 @@ int wash_set_option(int option, int64_t value)
             return fail(WASH_EINVAL, "tile coordinates must be 0 or a multiple of 256 in [256, 65536]");
         std::lock_guard<std::mutex> lock(g_mutex);
         g_tile_coords_option = value;
+        return WASH_OK;
+    }
+    if (option == WASH_OPT_GAP_BLOCKS) {
+        if (value != 0 && (value < 1 || value > 64 || (value & (value - 1)) != 0))
+            return fail(WASH_EINVAL, "gap blocks per wavefront must be 0 or a power of two in [1, 64]");
+        std::lock_guard<std::mutex> lock(g_mutex);
+        g_gap_blocks_option = value;
         return WASH_OK;
     }
     if (option == WASH_OPT_STREAM_MIN_BYTES) {

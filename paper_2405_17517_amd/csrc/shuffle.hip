@@ -58,9 +58,9 @@ __device__ __forceinline__ void gather_row_to_lds(const uint32_t *src, uint32_t 
 }
 
 // Gather, permute and scatter up to 64 queued coordinates, one per lane.
-template <bool kMomentum>
+template <bool kMomentum, typename QueueEntry>
 __device__ __forceinline__ void permute_batch(const ShuffleArgs &a, uint64_t tile_begin,
-                                              const uint32_t *queue, uint32_t nbatch,
+                                              const QueueEntry *queue, uint32_t nbatch,
                                               uint32_t *slab, uint32_t *slab_m)
 {
     const uint32_t lane = lane_id();
@@ -217,8 +217,7 @@ __global__ __launch_bounds__(kCountSlots) void fold_count_kernel(unsigned long l
 // that keeps the queue in ascending coordinate order, so the permute batches touch neighbouring
 // cache lines exactly as in the scanning kernel.
 
-constexpr int kListCap = 16;                 // finds a lane can park between two flushes
-constexpr int kGapQueueCap = kWave * kListCap;
+constexpr uint32_t kGapQueueCap = 512;       // finds a wavefront can park between two flushes, shared by its lanes
 
 template <bool kMomentum>
 __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_gap_kernel(const ShuffleArgs a)
@@ -232,11 +231,14 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_gap_kernel(con
     const uint64_t first_block = wave * bpw;
     if (first_block >= a.num_tiles) return;
 
+    // per wave: [queue: 512 x u16][lists: 512 x u16][slab(s)]; a lane's list holds 512 / blocks_per_wave finds
+    const uint32_t list_cap = kGapQueueCap / bpw;
     const uint32_t slab_words = a.N * kWave;
-    const uint32_t per_wave = kGapQueueCap + kWave * kListCap / 2 + slab_words * (kMomentum ? 2u : 1u);
-    uint32_t *queue = lds + wave_in_block * per_wave;
-    uint16_t *list = reinterpret_cast<uint16_t *>(queue + kGapQueueCap) + lane * kListCap;
-    uint32_t *slab = queue + kGapQueueCap + kWave * kListCap / 2;
+    const uint32_t per_wave = kGapQueueCap + slab_words * (kMomentum ? 2u : 1u);
+    uint32_t *base = lds + wave_in_block * per_wave;
+    uint16_t *queue = reinterpret_cast<uint16_t *>(base);
+    uint16_t *list = queue + kGapQueueCap + lane * list_cap;
+    uint32_t *slab = base + kGapQueueCap;
     uint32_t *slab_m = slab + slab_words;
     const uint64_t tile_begin = first_block * kGapPiece;
 
@@ -294,7 +296,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_gap_kernel(con
             }
         }
         // pour the lists into the queue when one is full or everybody is done
-        if (__ballot(parked == kListCap) == 0 && __ballot(active) != 0) continue;
+        if (__ballot(parked == list_cap) == 0 && __ballot(active) != 0) continue;
         uint32_t before = parked;                    // exclusive prefix of `parked` over the lanes
 #pragma unroll
         for (int off = 1; off < kWave; off <<= 1) {
@@ -303,7 +305,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_gap_kernel(con
         }
         const uint32_t total = __shfl(before, kWave - 1, kWave);
         before -= parked;
-        for (uint32_t j = 0; j < parked; ++j) queue[before + j] = lane * kGapPiece + list[j];
+        for (uint32_t j = 0; j < parked; ++j) queue[before + j] = static_cast<uint16_t>(lane * kGapPiece + list[j]);
         parked = 0;
         wave_lds_sync();
         for (uint32_t done = 0; done < total; done += kWave) {
@@ -346,8 +348,8 @@ hipError_t launch_shuffle_gap(const ShuffleArgs &a, hipStream_t stream)
     if (a.num_tiles == 0 || a.nsegs == 0) return hipSuccess;
     if (a.blocks_per_wave == 0 || a.blocks_per_wave > kWave || a.tile_coords != kGapPiece)
         return hipErrorInvalidValue;
-    const size_t per_wave = (kGapQueueCap + kWave * kListCap / 2 +
-                             static_cast<size_t>(a.N) * kWave * (a.momentum ? 2 : 1)) * sizeof(uint32_t);
+    if ((a.blocks_per_wave & (a.blocks_per_wave - 1)) != 0) return hipErrorInvalidValue;   // lists share 512 slots evenly
+    const size_t per_wave = (kGapQueueCap + static_cast<size_t>(a.N) * kWave * (a.momentum ? 2 : 1)) * sizeof(uint32_t);
     uint32_t waves = kWavesPerBlock;
     while (waves > 1 && per_wave * waves > 65536) waves >>= 1;
     if (per_wave * waves > 65536) return hipErrorInvalidConfiguration;
