@@ -1,12 +1,11 @@
 // wash_average (Alg. 1 output line) and papa_ema (Sec. 3, Eq. 1) for gfx950.
 //
 // Both are pure streaming passes bound by HBM bandwidth: every thread owns 4
-// consecutive coordinates, issues the N independent 16-byte loads of its column
-// block before using any of them, accumulates in fp64 in ascending n (the same
-// order and precision as the plain definition, so the fp32 result is the
-// correctly rounded one) and writes 16 bytes per row.  N is a template
-// parameter so the N values stay in registers: the EMA reads and writes each
-// element exactly once.  Rows are P elements apart and P need not be a multiple
+// consecutive coordinates, reads 16 bytes per row, accumulates in fp64 in
+// ascending n (the same order and precision as the plain definition, so the
+// fp32 result is the correctly rounded one) and writes 16 bytes per row.  For
+// the EMA N is a template parameter so the N values stay in registers: it reads
+// and writes each element exactly once.  Rows are P elements apart and P need not be a multiple
 // of 4, so the 16-byte accesses are only 4-byte aligned; gfx950 global memory
 // accepts that.
 #include "kernels.hpp"
@@ -38,38 +37,38 @@ __device__ __forceinline__ void store4(float *p, f4u v)
 // fp64 arithmetic is kept unfused so that it matches the definition operation by operation
 #pragma clang fp contract(off)
 
-template <int N>
+// One row at a time, one 16-byte load in flight per thread: the 32 KB vector L1 bounds what a
+// compute unit can have in flight anyway (256 lines), and reading the rows strictly one after
+// another measured 2 points faster than issuing all N loads at once.  N is a run-time value.
 __global__ __launch_bounds__(kThreads) void average_kernel(const float *__restrict__ params,
-                                                           float *__restrict__ out, uint64_t P)
+                                                           float *__restrict__ out, uint32_t N, uint64_t P)
 {
     const uint64_t base = (static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4u;
     if (base >= P) return;
-    const double inv_den = static_cast<double>(N);
+    const double den = static_cast<double>(N);
     if (base + 4u <= P) {
-        f4u v[N];
-#pragma unroll
-        for (int n = 0; n < N; ++n)
-            v[n] = load4<true>(params + static_cast<uint64_t>(n) * P + base);
         double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-#pragma unroll
-        for (int n = 0; n < N; ++n) {
-            s0 += static_cast<double>(v[n].x);
-            s1 += static_cast<double>(v[n].y);
-            s2 += static_cast<double>(v[n].z);
-            s3 += static_cast<double>(v[n].w);
+        const float *src = params + base;
+#pragma unroll 1
+        for (uint32_t n = 0; n < N; ++n) {
+            const f4u v = load4<true>(src);
+            src += P;
+            s0 += static_cast<double>(v.x);
+            s1 += static_cast<double>(v.y);
+            s2 += static_cast<double>(v.z);
+            s3 += static_cast<double>(v.w);
         }
         f4u o;
-        o.x = static_cast<float>(s0 / inv_den);
-        o.y = static_cast<float>(s1 / inv_den);
-        o.z = static_cast<float>(s2 / inv_den);
-        o.w = static_cast<float>(s3 / inv_den);
+        o.x = static_cast<float>(s0 / den);
+        o.y = static_cast<float>(s1 / den);
+        o.z = static_cast<float>(s2 / den);
+        o.w = static_cast<float>(s3 / den);
         store4<true>(out + base, o);
     } else {
         for (uint64_t g = base; g < P; ++g) {
             double s = 0.0;
-#pragma unroll
-            for (int n = 0; n < N; ++n) s += static_cast<double>(params[static_cast<uint64_t>(n) * P + g]);
-            out[g] = static_cast<float>(s / inv_den);
+            for (uint32_t n = 0; n < N; ++n) s += static_cast<double>(params[static_cast<uint64_t>(n) * P + g]);
+            out[g] = static_cast<float>(s / den);
         }
     }
 }
@@ -143,15 +142,6 @@ inline bool grid_for(uint64_t P, dim3 &grid)
 }
 
 template <int N>
-hipError_t run_average(const float *params, float *out, uint64_t P, hipStream_t stream)
-{
-    dim3 grid;
-    if (!grid_for(P, grid)) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL(average_kernel<N>, grid, dim3(kThreads), 0, stream, params, out, P);
-    return hipGetLastError();
-}
-
-template <int N>
 hipError_t run_ema(float *params, uint64_t P, double alpha, bool nt, hipStream_t stream)
 {
     dim3 grid;
@@ -177,12 +167,10 @@ hipError_t launch_copy(const float *src, float *dst, uint64_t n, hipStream_t str
 
 hipError_t launch_average(const float *params, float *out, uint32_t N, uint64_t P, hipStream_t stream)
 {
-    switch (N) {
-#define X(n) case n: return run_average<n>(params, out, P, stream);
-        WASH_FOR_EACH_N(X)
-#undef X
-    default: return hipErrorInvalidValue;
-    }
+    dim3 grid;
+    if (N == 0 || !grid_for(P, grid)) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(average_kernel, grid, dim3(kThreads), 0, stream, params, out, N, P);
+    return hipGetLastError();
 }
 
 hipError_t launch_ema(float *params, uint32_t N, uint64_t P, float alpha, bool nt, hipStream_t stream)
