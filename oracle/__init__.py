@@ -62,6 +62,10 @@ def lib():
         L.wash_shuffle_gap_ref_mt.restype = ctypes.c_int
         L.wash_ref_gap_mask.argtypes = [vp, u64, vp, u32, u64, u64]
         L.wash_ref_gap_mask.restype = ctypes.c_int
+        L.wash_consensus_sqdist_ref.argtypes = [vp, u32, u64, u64, u64, vp]
+        L.wash_consensus_sqdist_ref.restype = ctypes.c_int
+        L.wash_weighted_average_ref.argtypes = [vp, vp, vp, u32, u64]
+        L.wash_weighted_average_ref.restype = ctypes.c_int
         L.wash_average_ref.argtypes = [vp, vp, u32, u64]
         L.wash_average_ref.restype = ctypes.c_int
         L.papa_ema_ref.argtypes = [vp, u32, u64, ctypes.c_float]
@@ -219,3 +223,29 @@ def ema(params, alpha):
     if rc != 0:
         raise ValueError("papa_ema_ref: invalid argument")
     return params
+
+
+def consensus_sqdist(params, g_begin=0, g_end=None):
+    """float64 [N]: sum over coordinates [g_begin, g_end) of (theta_n - mean)^2."""
+    _check_pop(params, "params")
+    N, P = params.shape
+    if g_end is None:
+        g_end = P
+    out = np.zeros(N, dtype=np.float64)
+    rc = lib().wash_consensus_sqdist_ref(params.ctypes.data, N, P, int(g_begin), int(g_end), out.ctypes.data)
+    if rc != 0:
+        raise ValueError("wash_consensus_sqdist_ref: invalid argument")
+    return out
+
+
+def weighted_average(params, weights):
+    _check_pop(params, "params")
+    N, P = params.shape
+    w = np.ascontiguousarray(np.asarray(weights, dtype=np.float64))
+    if w.shape != (N,):
+        raise ValueError("need N weights")
+    out = np.empty(P, dtype=np.float32)
+    rc = lib().wash_weighted_average_ref(params.ctypes.data, w.ctypes.data, out.ctypes.data, N, P)
+    if rc != 0:
+        raise ValueError("wash_weighted_average_ref: invalid argument")
+    return out

@@ -17,6 +17,9 @@
  *   - uniform average         : Alg. 1 output line; consensus definition
  *                               below Eq. 1
  *   - PAPA EMA                : Sec. 3, Eq. 1
+ *   - distance to consensus   : the quantity of Eq. 2, Eq. 5 and Fig. 2
+ *   - weighted average        : convex combinations of the models (appendix,
+ *                               interpolation heatmaps)
  *
  * The paper fixes only the LAW of the shuffle.  A bit-exact comparison needs
  * one concrete random stream; the one defined here ("stream v1") is this
@@ -444,6 +447,52 @@ int papa_ema_ref(float *params, uint32_t N, uint64_t P, float alpha)
             double x = (double)params[(uint64_t)n * P + g];
             params[(uint64_t)n * P + g] = (float)(a * x + (1.0 - a) * mean);
         }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/*
+ * Distance to the consensus (the paper's diagnostic: Fig. 2 plots
+ * (1/N) sum_n ||theta_n - mean||, Eq. 2 and Eq. 5 are statements about
+ * sum_n ||theta_n - mean||^2; the layer-schedule figure uses slices of the
+ * parameter vector).  out[n] = sum over g in [g_begin, g_end) of
+ * (theta[n][g] - mean[g])^2, everything in fp64, mean[g] = (sum_n theta[n][g]) / N
+ * unrounded.  The caller takes square roots / averages over n as needed.
+ */
+int wash_consensus_sqdist_ref(const float *params, uint32_t N, uint64_t P,
+                              uint64_t g_begin, uint64_t g_end, double *out)
+{
+    if (params == NULL || out == NULL || N == 0 || P == 0) return -1;
+    if (g_begin > g_end || g_end > P) return -1;
+    for (uint32_t n = 0; n < N; ++n) out[n] = 0.0;
+    for (uint64_t g = g_begin; g < g_end; ++g) {
+        double sum = 0.0;
+        for (uint32_t n = 0; n < N; ++n) sum += (double)params[(uint64_t)n * P + g];
+        double mean = sum / (double)N;
+        for (uint32_t n = 0; n < N; ++n) {
+            double d = (double)params[(uint64_t)n * P + g] - mean;
+            out[n] += d * d;
+        }
+    }
+    return 0;
+}
+
+/*
+ * Weighted combination of the models (the interpolation study of the appendix
+ * evaluates arbitrary convex combinations; GreedySoup-style soups average a
+ * subset): out[g] = sum_n w[n] * theta[n][g], products and sum in fp64 in
+ * ascending n, rounded once to fp32.  w = (1/N, ..., 1/N) is the uniform
+ * average up to the rounding of 1/N.
+ */
+int wash_weighted_average_ref(const float *params, const double *w, float *out, uint32_t N, uint64_t P)
+{
+    if (params == NULL || w == NULL || out == NULL || N == 0 || P == 0) return -1;
+    for (uint32_t n = 0; n < N; ++n) if (!(w[n] == w[n]) || w[n] - w[n] != 0.0) return -1; /* NaN or infinite */
+    for (uint64_t g = 0; g < P; ++g) {
+        double sum = 0.0;
+        for (uint32_t n = 0; n < N; ++n) sum += w[n] * (double)params[(uint64_t)n * P + g];
+        out[g] = (float)sum;
     }
     return 0;
 }
