@@ -12,7 +12,9 @@
  *   wash_average   the final uniform average     (Alg. 1, output line)
  *   papa_ema       PAPA's EMA toward the mean    (Sec. 3, Eq. 1)  -- comparison baseline
  *
- * and one host helper gives the layer-wise probabilities of Eq. 6.
+ * one host helper gives the layer-wise probabilities of Eq. 6, and two further
+ * passes serve the paper's analysis: wash_consensus_sqdist (Eq. 2, Eq. 5) and
+ * wash_weighted_average (interpolations between the models).
  *
  * Conventions for every entry point
  *   - "device" pointers are HIP device memory on the CURRENT device of the
@@ -134,6 +136,37 @@ int wash_average(const float *params, float *out, uint32_t N, uint64_t P, void *
  * Errors: WASH_EINVAL for NULL params, N = 0 or > WASH_MAX_N, P = 0, alpha NaN or infinite.
  */
 int papa_ema(float *params, uint32_t N, uint64_t P, float alpha, void *stream);
+
+/*
+ * Distance to the consensus, the diagnostic behind Eq. 2, Eq. 5 and the
+ * distance-to-consensus figures (which also look at slices of the parameter
+ * vector): out[n] = sum over g in [g_begin, g_end) of (params[n][g] - mean[g])^2,
+ * mean[g] = (1/N) sum_n params[n][g], everything in fp64.  The caller takes
+ * sqrt / averages over n (the figures plot (1/N) sum_n sqrt(out[n])).  The
+ * reduction has a fixed shape: the same input gives the same bits every time.
+ *   params  device, [N, P] fp32 (read only)    out  device, N doubles (overwritten)
+ *   g_begin <= g_end <= P   (an empty slice gives zeros)
+ * Uses 1 MiB of library-owned device scratch per device: calls that overlap on
+ * one GPU (different streams) race on it.
+ * Errors: WASH_EINVAL for NULL pointers, N = 0 or > WASH_MAX_N, P = 0, a slice
+ * outside [0, P]; WASH_EHIP if the scratch cannot be allocated or a launch fails.
+ */
+int wash_consensus_sqdist(const float *params, uint32_t N, uint64_t P,
+                          uint64_t g_begin, uint64_t g_end, double *out, void *stream);
+
+/*
+ * Weighted combination of the models: out[g] = sum_n weights[n] * params[n][g],
+ * products and sum in fp64 in ascending n, rounded once to fp32.  Convex
+ * weights give the interpolations studied in the appendix; a 0/1-over-k vector
+ * gives a soup over a subset; weights 1/N give the uniform average up to the
+ * rounding of 1/N (wash_average divides the sum instead).
+ *   params   device, [N, P] fp32 (read only)    out  device, [P] fp32, must not overlap params
+ *   weights  HOST array of N finite doubles, read before the call returns
+ * Errors: WASH_EINVAL for NULL pointers, N = 0 or > WASH_MAX_N, P = 0, a
+ * non-finite weight.
+ */
+int wash_weighted_average(const float *params, const double *weights, float *out,
+                          uint32_t N, uint64_t P, void *stream);
 
 /*
  * Layer-wise probabilities, Eq. 6 (host only): out[l] for l = 0 .. L-1.

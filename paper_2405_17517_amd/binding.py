@@ -42,6 +42,10 @@ def _load():
     L.wash_average.restype = ctypes.c_int
     L.papa_ema.argtypes = [vp, u32, u64, ctypes.c_float, vp]
     L.papa_ema.restype = ctypes.c_int
+    L.wash_consensus_sqdist.argtypes = [vp, u32, u64, u64, u64, vp, vp]
+    L.wash_consensus_sqdist.restype = ctypes.c_int
+    L.wash_weighted_average.argtypes = [vp, vp, vp, u32, u64, vp]
+    L.wash_weighted_average.restype = ctypes.c_int
     L.wash_copy_f32.argtypes = [vp, vp, u64, vp]
     L.wash_copy_f32.restype = ctypes.c_int
     L.wash_layer_probs.argtypes = [ctypes.c_double, u32, ctypes.c_int, vp]
@@ -144,6 +148,42 @@ def papa_ema(params: torch.Tensor, alpha: float) -> None:
     with torch.cuda.device(params.device):
         rc = _lib.papa_ema(params.data_ptr(), N, P, float(alpha), _stream(params))
     _check(rc, "papa_ema")
+
+
+def wash_consensus_sqdist(params: torch.Tensor, g_begin: int = 0, g_end: Optional[int] = None,
+                          out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """float64 [N] on the GPU: sum over the slice of (theta_n - mean)^2 (Eq. 2 / Eq. 5 quantity)."""
+    N, P = _dev_pop(params, "params")
+    if g_end is None:
+        g_end = P
+    if out is None:
+        out = torch.empty(N, dtype=torch.float64, device=params.device)
+    elif not (out.is_cuda and out.dtype == torch.float64 and out.is_contiguous() and out.numel() == N
+              and out.device == params.device):
+        raise TypeError("out: need a contiguous float64 [N] tensor on the same GPU")
+    with torch.cuda.device(params.device):
+        rc = _lib.wash_consensus_sqdist(params.data_ptr(), N, P, int(g_begin), int(g_end), out.data_ptr(),
+                                        _stream(params))
+    _check(rc, "wash_consensus_sqdist")
+    return out
+
+
+def wash_weighted_average(params: torch.Tensor, weights: Sequence[float],
+                          out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """out[g] = sum_n weights[n] * params[n][g] (fp64 accumulation); returns out [P]."""
+    N, P = _dev_pop(params, "params")
+    if len(weights) != N:
+        raise TypeError("need one weight per model")
+    w = (ctypes.c_double * N)(*[float(x) for x in weights])
+    if out is None:
+        out = torch.empty(P, dtype=torch.float32, device=params.device)
+    elif not (out.is_cuda and out.dtype == torch.float32 and out.is_contiguous() and out.numel() == P
+              and out.device == params.device):
+        raise TypeError("out: need a contiguous float32 [P] tensor on the same GPU")
+    with torch.cuda.device(params.device):
+        rc = _lib.wash_weighted_average(params.data_ptr(), ctypes.addressof(w), out.data_ptr(), N, P, _stream(params))
+    _check(rc, "wash_weighted_average")
+    return out
 
 
 def wash_copy_f32(src: torch.Tensor, dst: torch.Tensor) -> None:

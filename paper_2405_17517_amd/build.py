@@ -10,7 +10,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libwash_hip.so")
-SOURCES = ["api.hip", "shuffle.hip", "reduce.hip"]
+SOURCES = ["api.hip", "shuffle.hip", "reduce.hip", "diagnostics.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -135,6 +135,33 @@ int get_table(int device, uint64_t P, uint32_t tile_coords, bool gap, std::vecto
     return WASH_OK;
 }
 
+// One scratch buffer per device for the partial sums of wash_consensus_sqdist (1 MiB, kept until shutdown).
+struct Scratch {
+    int device;
+    void *dev;
+};
+std::vector<Scratch> g_scratch;
+
+int get_scratch(int device, double **out)
+{
+    for (const Scratch &sc : g_scratch)
+        if (sc.device == device) {
+            *out = static_cast<double *>(sc.dev);
+            return WASH_OK;
+        }
+    void *dev = nullptr;
+    const hipError_t e = hipMalloc(&dev, wash::kSqdistScratchBytes);
+    if (e != hipSuccess) return fail_hip("hipMalloc(scratch)", e);
+    try {
+        g_scratch.push_back(Scratch{device, dev});
+    } catch (const std::bad_alloc &) {
+        (void)hipFree(dev);
+        return fail(WASH_ENOMEM, "scratch list");
+    }
+    *out = static_cast<double *>(dev);
+    return WASH_OK;
+}
+
 bool ranges_overlap(const void *a, uint64_t abytes, const void *b, uint64_t bbytes)
 {
     const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
@@ -302,6 +329,45 @@ int papa_ema(float *params, uint32_t N, uint64_t P, float alpha, void *stream)
     return WASH_OK;
 }
 
+int wash_consensus_sqdist(const float *params, uint32_t N, uint64_t P, uint64_t g_begin, uint64_t g_end,
+                          double *out, void *stream)
+{
+    g_detail[0] = 0;
+    if (int rc = check_population(params, N, P)) return rc;
+    if (out == nullptr) return fail(WASH_EINVAL, "out is NULL");
+    if (g_begin > g_end || g_end > P) return fail(WASH_EINVAL, "slice outside [0,P]");
+    if (ranges_overlap(params, static_cast<uint64_t>(N) * P * sizeof(float), out, N * sizeof(double)))
+        return fail(WASH_EINVAL, "out overlaps params");
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return fail_hip("hipGetDevice", e);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    double *partial = nullptr;
+    if (int rc = get_scratch(device, &partial)) return rc;
+    e = wash::launch_sqdist(params, N, P, g_begin, g_end, partial, out, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip("wash_consensus_sqdist launch", e);
+    return WASH_OK;
+}
+
+int wash_weighted_average(const float *params, const double *weights, float *out, uint32_t N, uint64_t P,
+                          void *stream)
+{
+    g_detail[0] = 0;
+    if (int rc = check_population(params, N, P)) return rc;
+    if (out == nullptr) return fail(WASH_EINVAL, "out is NULL");
+    if (weights == nullptr) return fail(WASH_EINVAL, "weights is NULL");
+    if (ranges_overlap(params, static_cast<uint64_t>(N) * P * sizeof(float), out, P * sizeof(float)))
+        return fail(WASH_EINVAL, "out overlaps params");
+    wash::Weights w{};
+    for (uint32_t n = 0; n < N; ++n) {
+        if (!std::isfinite(weights[n])) return fail(WASH_EINVAL, "weight %u is not finite", n);
+        w.w[n] = weights[n];
+    }
+    const hipError_t e = wash::launch_weighted_average(params, out, N, P, w, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip("wash_weighted_average launch", e);
+    return WASH_OK;
+}
+
 int wash_copy_f32(const float *src, float *dst, uint64_t n, void *stream)
 {
     g_detail[0] = 0;
@@ -382,6 +448,10 @@ int wash_shutdown(void)
         if (hipSetDevice(t.key.device) != hipSuccess || hipFree(t.dev) != hipSuccess) rc = WASH_EHIP;
     }
     g_tables.clear();
+    for (Scratch &sc : g_scratch) {
+        if (hipSetDevice(sc.device) != hipSuccess || hipFree(sc.dev) != hipSuccess) rc = WASH_EHIP;
+    }
+    g_scratch.clear();
     if (have_current) (void)hipSetDevice(current);
     return rc;
 }

@@ -1,0 +1,182 @@
+// Two more bandwidth-bound passes over the population, built on the same access pattern as
+// the average and the EMA:
+//   consensus_sqdist   out[n] = sum_g (theta[n][g] - mean[g])^2  -- the quantity of Eq. 2 and
+//                      Eq. 5 and of the distance-to-consensus figures; fp64 throughout
+//   weighted_average   out[g] = sum_n w[n] theta[n][g]            -- convex combinations of the
+//                      models (interpolation study, soups); fp64, rounded once
+#include "kernels.hpp"
+
+namespace wash {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWave = 64;
+
+typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+
+#pragma clang fp contract(off)
+
+__global__ __launch_bounds__(kThreads) void weighted_average_kernel(const float *__restrict__ params,
+                                                                    float *__restrict__ out, uint32_t N,
+                                                                    uint64_t P, const Weights w)
+{
+    const uint64_t base = (static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4u;
+    if (base >= P) return;
+    if (base + 4u <= P) {
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+        const float *src = params + base;
+#pragma unroll 1
+        for (uint32_t n = 0; n < N; ++n) {
+            const f4u v = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(src));
+            src += P;
+            const double wn = w.w[n];
+            s0 += wn * static_cast<double>(v.x);
+            s1 += wn * static_cast<double>(v.y);
+            s2 += wn * static_cast<double>(v.z);
+            s3 += wn * static_cast<double>(v.w);
+        }
+        f4u o;
+        o.x = static_cast<float>(s0);
+        o.y = static_cast<float>(s1);
+        o.z = static_cast<float>(s2);
+        o.w = static_cast<float>(s3);
+        __builtin_nontemporal_store(o, reinterpret_cast<f4u *>(out + base));
+    } else {
+        for (uint64_t g = base; g < P; ++g) {
+            double s = 0.0;
+            for (uint32_t n = 0; n < N; ++n) s += w.w[n] * static_cast<double>(params[static_cast<uint64_t>(n) * P + g]);
+            out[g] = static_cast<float>(s);
+        }
+    }
+}
+
+// Every block walks chunks of 1024 coordinates (grid-stride), every thread keeps N fp64
+// accumulators; a fixed-shape reduction (lanes, then waves, then blocks in a second kernel)
+// makes the result independent of scheduling, so two runs give the same bits.
+template <int N>
+__global__ __launch_bounds__(kThreads) void sqdist_partial_kernel(const float *__restrict__ params, uint64_t P,
+                                                                  uint64_t g_begin, uint64_t g_end,
+                                                                  double *__restrict__ partial)
+{
+    __shared__ double stage[kThreads / kWave][N];
+    double acc[N];
+#pragma unroll
+    for (int n = 0; n < N; ++n) acc[n] = 0.0;
+    const double den = static_cast<double>(N);
+    const uint64_t span = g_end - g_begin;
+    const uint64_t nchunks = (span + kThreads * 4u - 1) / (kThreads * 4u);
+    for (uint64_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
+        const uint64_t off = (c * kThreads + threadIdx.x) * 4u;
+        if (off >= span) continue;
+        const uint64_t base = g_begin + off;
+        if (off + 4u <= span) {
+            f4u v[N];
+#pragma unroll
+            for (int n = 0; n < N; ++n)
+                v[n] = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(params + static_cast<uint64_t>(n) * P + base));
+            double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+#pragma unroll
+            for (int n = 0; n < N; ++n) {
+                s0 += static_cast<double>(v[n].x);
+                s1 += static_cast<double>(v[n].y);
+                s2 += static_cast<double>(v[n].z);
+                s3 += static_cast<double>(v[n].w);
+            }
+            const double m0 = s0 / den, m1 = s1 / den, m2 = s2 / den, m3 = s3 / den;
+#pragma unroll
+            for (int n = 0; n < N; ++n) {
+                const double d0 = static_cast<double>(v[n].x) - m0, d1 = static_cast<double>(v[n].y) - m1;
+                const double d2 = static_cast<double>(v[n].z) - m2, d3 = static_cast<double>(v[n].w) - m3;
+                acc[n] += ((d0 * d0 + d1 * d1) + d2 * d2) + d3 * d3;
+            }
+        } else {
+            for (uint64_t g = base; g < g_end; ++g) {
+                double s = 0.0;
+#pragma unroll
+                for (int n = 0; n < N; ++n) s += static_cast<double>(params[static_cast<uint64_t>(n) * P + g]);
+                const double m = s / den;
+#pragma unroll
+                for (int n = 0; n < N; ++n) {
+                    const double d = static_cast<double>(params[static_cast<uint64_t>(n) * P + g]) - m;
+                    acc[n] += d * d;
+                }
+            }
+        }
+    }
+    const uint32_t lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+#pragma unroll
+    for (int n = 0; n < N; ++n) {
+        double v = acc[n];
+#pragma unroll
+        for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_down(v, o, kWave);
+        if (lane == 0) stage[wave][n] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < N) {
+        double v = stage[0][threadIdx.x];
+        for (int w = 1; w < kThreads / kWave; ++w) v += stage[w][threadIdx.x];
+        partial[static_cast<uint64_t>(blockIdx.x) * N + threadIdx.x] = v;
+    }
+}
+
+// out[n] = sum over blocks of partial[b][n], pairwise in a fixed order (one wave per model).
+__global__ __launch_bounds__(kWave) void sqdist_final_kernel(const double *__restrict__ partial, uint32_t nblocks,
+                                                             uint32_t N, double *__restrict__ out)
+{
+    const uint32_t n = blockIdx.x;
+    double v = 0.0;
+    for (uint32_t b = threadIdx.x; b < nblocks; b += kWave) v += partial[static_cast<uint64_t>(b) * N + n];
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_down(v, o, kWave);
+    if (threadIdx.x == 0) out[n] = v;
+}
+
+template <int N>
+hipError_t run_sqdist(const float *params, uint64_t P, uint64_t g_begin, uint64_t g_end, double *partial,
+                      uint32_t nblocks, double *out, hipStream_t stream)
+{
+    hipLaunchKernelGGL(sqdist_partial_kernel<N>, dim3(nblocks), dim3(kThreads), 0, stream, params, P, g_begin, g_end,
+                       partial);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(sqdist_final_kernel, dim3(N), dim3(kWave), 0, stream, partial, nblocks, static_cast<uint32_t>(N), out);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+uint32_t sqdist_blocks(uint64_t span)
+{
+    const uint64_t nchunks = (span + kThreads * 4u - 1) / (kThreads * 4u);
+    return static_cast<uint32_t>(nchunks < kSqdistMaxBlocks ? (nchunks ? nchunks : 1) : kSqdistMaxBlocks);
+}
+
+hipError_t launch_weighted_average(const float *params, float *out, uint32_t N, uint64_t P, const Weights &w,
+                                   hipStream_t stream)
+{
+    const uint64_t threads = (P + 3u) / 4u;
+    const uint64_t blocks = (threads + kThreads - 1) / kThreads;
+    if (N == 0 || N > 32 || blocks == 0 || blocks > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(weighted_average_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, stream, params,
+                       out, N, P, w);
+    return hipGetLastError();
+}
+
+#define WASH_FOR_EACH_N(X)                                                                         \
+    X(1) X(2) X(3) X(4) X(5) X(6) X(7) X(8) X(9) X(10) X(11) X(12) X(13) X(14) X(15) X(16) X(17)   \
+    X(18) X(19) X(20) X(21) X(22) X(23) X(24) X(25) X(26) X(27) X(28) X(29) X(30) X(31) X(32)
+
+hipError_t launch_sqdist(const float *params, uint32_t N, uint64_t P, uint64_t g_begin, uint64_t g_end,
+                         double *partial, double *out, hipStream_t stream)
+{
+    const uint32_t nblocks = sqdist_blocks(g_end - g_begin);
+    switch (N) {
+#define X(n) case n: return run_sqdist<n>(params, P, g_begin, g_end, partial, nblocks, out, stream);
+        WASH_FOR_EACH_N(X)
+#undef X
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace wash

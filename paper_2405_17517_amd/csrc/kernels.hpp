@@ -41,6 +41,20 @@ constexpr size_t kCountSlotBytes = static_cast<size_t>(kCountSlots) * kCountSlot
 hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream);
 hipError_t launch_shuffle_gap(const ShuffleArgs &a, hipStream_t stream);
 hipError_t launch_average(const float *params, float *out, uint32_t N, uint64_t P, hipStream_t stream);
+// weights of wash_weighted_average, passed by value as a kernel argument
+struct Weights {
+    double w[32];
+};
+hipError_t launch_weighted_average(const float *params, float *out, uint32_t N, uint64_t P, const Weights &w,
+                                   hipStream_t stream);
+
+// consensus distance: `partial` is scratch of kSqdistMaxBlocks * 32 doubles
+constexpr uint32_t kSqdistMaxBlocks = 4096;
+constexpr size_t kSqdistScratchBytes = static_cast<size_t>(kSqdistMaxBlocks) * 32 * sizeof(double);
+uint32_t sqdist_blocks(uint64_t span);
+hipError_t launch_sqdist(const float *params, uint32_t N, uint64_t P, uint64_t g_begin, uint64_t g_end,
+                         double *partial, double *out, hipStream_t stream);
+
 hipError_t launch_copy(const float *src, float *dst, uint64_t n, hipStream_t stream);
 hipError_t launch_ema(float *params, uint32_t N, uint64_t P, float alpha, bool nontemporal, hipStream_t stream);
 
