@@ -121,6 +121,24 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
     wall = time.perf_counter() - wall0
     total_ms = t0.elapsed_time(t1)
 
+    # the two analysis passes, timed on their own after the timed region (not part of a step)
+    reps = 5
+    weights = [1.0 / N] * N
+    extra = {}
+    for name, fn in (("wash_consensus_sqdist", lambda: wash.wash_consensus_sqdist(pop)),
+                     ("wash_weighted_average", lambda: wash.wash_weighted_average(pop, weights, out))):
+        fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / reps
+        nbytes = N * P * 4.0 if name == "wash_consensus_sqdist" else (N + 1.0) * P * 4.0
+        extra[name] = {"avg_us": ms * 1e3, "alg_bytes": nbytes, "achieved": nbytes / (ms * 1e-3) / 1e9,
+                       "frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
     avg_ms = {k: sum(tm.ms(k)) / steps for k in ("wash_shuffle", "papa_ema", "wash_average")}
     med_ms = {k: _median(tm.ms(k)) for k in avg_ms}
     selected = int(cnt.item()) / steps
@@ -138,6 +156,7 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
         "population_bytes": N * P * 4 * bufs,
         "cache_resident": N * P * 4 * bufs <= 256 * (1 << 20),
         "roofline": kernel_rooflines(N, P, bufs, frac_sel, avg_ms),
+        "analysis_passes": extra,
     }
     del pop, mom, ema_buf, out
     torch.cuda.empty_cache()
@@ -285,6 +304,7 @@ def main():
         "roofline": roofline,
         "roofline_per_kernel": {k: {kk: vv for kk, vv in v.items()} | {"traffic": load_traffic(workload_key, k)}
                                 for k, v in roof.items()},
+        "analysis_passes": main_res["analysis_passes"],
         "copy_yardstick": yard,
     }
 
