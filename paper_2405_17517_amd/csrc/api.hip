@@ -276,13 +276,13 @@ static int shuffle_common(bool gap, float *params, float *momentum, uint32_t N, 
     a.selected_count = reinterpret_cast<unsigned long long *>(selected_count);
     a.count_slots = selected_count ? reinterpret_cast<unsigned long long *>(base) : nullptr;
     if (gap) {
-        // a wavefront walks up to 64 restart blocks; fewer when that would leave the 1024 SIMDs short of
-        // wavefronts (a wavefront's time is set by the longest walk and one memory round trip, not by its width)
+        // Blocks walked by one wavefront.  The kernel is bound by the scattered read-modify-write rate as soon
+        // as a few coordinates per block are selected, and that rate grows with the number of batches in
+        // flight, i.e. with the number of wavefronts: aim at about 16 finds per wavefront (measured best from
+        // p = 1e-3 to 1e-1), and never leave the 1024 SIMDs short of wavefronts when p is tiny.
         uint32_t bpw = 64;
+        while (bpw > 1 && static_cast<double>(bpw) * wash::kGapPiece * p_max > 16.0) bpw >>= 1;
         while (bpw > 1 && a.num_tiles / bpw < 2048) bpw >>= 1;
-        // the 512 list slots of a wavefront are shared by its lanes: at high p fewer, longer lists keep the
-        // finds of one cache line in one batch (a lane's list should span several 32-coordinate lines)
-        while (bpw > 8 && static_cast<double>(bpw) * p_max > 0.5) bpw >>= 1;
         if (g_gap_blocks_option != 0) bpw = static_cast<uint32_t>(g_gap_blocks_option);
         a.blocks_per_wave = bpw;
         e = wash::launch_shuffle_gap(a, static_cast<hipStream_t>(stream));

@@ -79,8 +79,11 @@ __device__ __forceinline__ void permute_batch(const ShuffleArgs &a, uint64_t til
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // descending Fisher-Yates on the values themselves: swapping slab rows i and j keeps
-    // slab[n] == old[perm[n]]; row i is final after step i and goes straight to memory
+    // slab[n] == old[perm[n]]; row i is final after step i and goes straight to memory.
+    // A row that keeps its own value (a fixed point of the permutation: one per coordinate on
+    // average) is not written: `moved` has bit k set once slot k holds a value from another row.
     const uint32_t g_lo = static_cast<uint32_t>(g), g_hi = static_cast<uint32_t>(g >> 32);
+    uint32_t moved = 0;
     uint32_t i = N - 1;
     for (uint32_t call = 0; i > 0; ++call) {
         const Words4 r = philox4x32_10(g_lo, g_hi, a.step, 1u + call, a.key_lo, a.key_hi);
@@ -89,21 +92,25 @@ __device__ __forceinline__ void permute_batch(const ShuffleArgs &a, uint64_t til
         for (int k = 0; k < 4; ++k) {
             if (i == 0) break;
             const uint32_t j = __umulhi(w[k], i + 1u);
+            const bool write_row = (j != i) || ((moved >> i) & 1u);
             const uint32_t vi = slab[i * kWave + lane];
             const uint32_t vj = slab[j * kWave + lane];
-            col[static_cast<uint64_t>(i) * P] = vj;
+            if (write_row) col[static_cast<uint64_t>(i) * P] = vj;
             slab[j * kWave + lane] = vi;
             if (kMomentum) {
                 const uint32_t mi = slab_m[i * kWave + lane];
                 const uint32_t mj = slab_m[j * kWave + lane];
-                col_m[static_cast<uint64_t>(i) * P] = mj;
+                if (write_row) col_m[static_cast<uint64_t>(i) * P] = mj;
                 slab_m[j * kWave + lane] = mi;
             }
+            if (j != i) moved |= 1u << j;
             --i;
         }
     }
-    col[0] = slab[lane];
-    if (kMomentum) col_m[0] = slab_m[lane];
+    if (moved & 1u) {
+        col[0] = slab[lane];
+        if (kMomentum) col_m[0] = slab_m[lane];
+    }
 }
 
 template <bool kMomentum>
@@ -119,9 +126,11 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
     if (first == kNoSegment) return;
 
     const uint32_t slab_words = a.N * kWave;
-    const uint32_t per_wave = kQueueCap + slab_words * (kMomentum ? 2u : 1u);
-    uint32_t *queue = lds + wave_in_block * per_wave;
-    uint32_t *slab = queue + kQueueCap;
+    // per wave: [queue: 320 x u16 (tile offsets; a tile has at most 65536 coordinates)][slab(s)]
+    const uint32_t per_wave = kQueueCap / 2 + slab_words * (kMomentum ? 2u : 1u);
+    uint32_t *base = lds + wave_in_block * per_wave;
+    uint16_t *queue = reinterpret_cast<uint16_t *>(base);
+    uint32_t *slab = base + kQueueCap / 2;
     uint32_t *slab_m = slab + slab_words;
 
     const uint64_t tile_begin = tile * a.tile_coords;
@@ -167,7 +176,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
         const uint32_t off0 = static_cast<uint32_t>(g0 - tile_begin);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            if (sel[k]) queue[pos++] = off0 + k;
+            if (sel[k]) queue[pos++] = static_cast<uint16_t>(off0 + k);
         }
         queued += __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3);
         while (queued >= kWave) {
@@ -325,7 +334,7 @@ hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream)
 {
     if (a.num_tiles == 0 || a.nsegs == 0) return hipSuccess;
     // the direct-to-LDS loads address LDS through a 16-bit offset: keep a block's partition below 64 KiB
-    const size_t per_wave = (kQueueCap + static_cast<size_t>(a.N) * kWave * (a.momentum ? 2 : 1)) * sizeof(uint32_t);
+    const size_t per_wave = (kQueueCap / 2 + static_cast<size_t>(a.N) * kWave * (a.momentum ? 2 : 1)) * sizeof(uint32_t);
     uint32_t waves = kWavesPerBlock;
     while (waves > 1 && per_wave * waves > 65536) waves >>= 1;
     if (per_wave * waves > 65536) return hipErrorInvalidConfiguration;
