@@ -291,7 +291,7 @@ def main():
         "value": main_res["pass_coords_per_s"], "unit": "coords/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32 storage, u32 moves, f64 accumulation", "data": "synthetic",
+        "vs_baseline": None, "dtype": "f64", "storage_dtype": "f32 (shuffle moves raw 32-bit words)", "data": "synthetic",
         "config": {"workload": f"config {cfg.index}: {cfg.name}, N={cfg.N}, P={cfg.P}, "
                                f"{main_res['segments']} tensors, p={args.p if args.p is not None else 'as listed'}, "
                                f"{'params+momentum' if cfg.momentum else 'params only'}; "

@@ -27,6 +27,7 @@ namespace {
 
 constexpr int kWave = 64;
 constexpr int kWavesPerBlock = 4;
+constexpr uint32_t kMaxCalls = 8;       // Philox calls for the N-1 <= 31 permutation words of a coordinate
 constexpr int kQueueCap = 64 + 256;   // a batch is cut as soon as 64 are queued; one scan adds <= 256
 
 __device__ __forceinline__ uint32_t lane_id() { return __lane_id(); }
@@ -76,22 +77,46 @@ __device__ __forceinline__ void permute_batch(const ShuffleArgs &a, uint64_t til
         gather_row_to_lds(col + static_cast<uint64_t>(n) * P, slab + n * kWave);
         if (kMomentum) gather_row_to_lds(col_m + static_cast<uint64_t>(n) * P, slab_m + n * kWave);
     }
+    // While the gathers are in flight, draw the permutation words and reduce them to the swap
+    // partners j_i of the descending Fisher-Yates walk (i = N-1 .. 1, j_i = (w * (i+1)) >> 32,
+    // four per Philox call, packed one byte each): they depend on the coordinate only.  The packs
+    // sit in a register ring that is rotated instead of indexed, so both loops stay rolled.
+    const uint32_t g_lo = static_cast<uint32_t>(g), g_hi = static_cast<uint32_t>(g >> 32);
+    const uint32_t nswaps = N - 1;
+    const uint32_t ncalls = (nswaps + 3u) / 4u;             // <= kMaxCalls
+    uint32_t ring[kMaxCalls] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (uint32_t call = 0; call < kMaxCalls; ++call) {
+        // after kMaxCalls rotations the pack of call c sits in ring[c]
+        uint32_t pack = 0;
+        if (call < ncalls) {
+            const Words4 r = philox4x32_10(g_lo, g_hi, a.step, 1u + call, a.key_lo, a.key_hi);
+            const uint32_t w[4] = {r.w0, r.w1, r.w2, r.w3};
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k) {
+                const uint32_t t = call * 4u + k;
+                if (t < nswaps) pack |= __umulhi(w[k], N - t) << (8u * k);   // i + 1 = N - t
+            }
+        }
+#pragma unroll
+        for (uint32_t q = 0; q + 1 < kMaxCalls; ++q) ring[q] = ring[q + 1];
+        ring[kMaxCalls - 1] = pack;
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
-    // descending Fisher-Yates on the values themselves: swapping slab rows i and j keeps
+    // The walk is applied to the values themselves: swapping slab rows i and j keeps
     // slab[n] == old[perm[n]]; row i is final after step i and goes straight to memory.
     // A row that keeps its own value (a fixed point of the permutation: one per coordinate on
     // average) is not written: `moved` has bit k set once slot k holds a value from another row.
-    const uint32_t g_lo = static_cast<uint32_t>(g), g_hi = static_cast<uint32_t>(g >> 32);
     uint32_t moved = 0;
-    uint32_t i = N - 1;
-    for (uint32_t call = 0; i > 0; ++call) {
-        const Words4 r = philox4x32_10(g_lo, g_hi, a.step, 1u + call, a.key_lo, a.key_hi);
-        const uint32_t w[4] = {r.w0, r.w1, r.w2, r.w3};
+    uint32_t i = nswaps;
+    for (uint32_t call = 0; call < ncalls; ++call) {
+        const uint32_t pack = ring[0];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (uint32_t q = 0; q + 1 < kMaxCalls; ++q) ring[q] = ring[q + 1];
+#pragma unroll
+        for (uint32_t k = 0; k < 4; ++k) {
             if (i == 0) break;
-            const uint32_t j = __umulhi(w[k], i + 1u);
+            const uint32_t j = (pack >> (8u * k)) & 0xFFu;
             const bool write_row = (j != i) || ((moved >> i) & 1u);
             const uint32_t vi = slab[i * kWave + lane];
             const uint32_t vj = slab[j * kWave + lane];
