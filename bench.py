@@ -139,6 +139,28 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
         extra[name] = {"avg_us": ms * 1e3, "alg_bytes": nbytes, "achieved": nbytes / (ms * 1e-3) / 1e9,
                        "frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
+    # the same step captured once in a HIP graph and replayed (the step number is frozen in the
+    # graph, so this is a launch-overhead measurement, not a training loop)
+    graph_ms = None
+    try:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            do_shuffle()
+            do_ema()
+            do_avg()
+        g.replay()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps_g = max(5, min(steps, 50))
+        a.record()
+        for _ in range(reps_g):
+            g.replay()
+        b.record()
+        torch.cuda.synchronize()
+        graph_ms = a.elapsed_time(b) / reps_g
+        del g
+    except Exception as exc:  # noqa: BLE001  (a failed capture must not cost the measurement)
+        print(f"[bench] graph capture skipped: {exc}", file=sys.stderr)
+
     avg_ms = {k: sum(tm.ms(k)) / steps for k in ("wash_shuffle", "papa_ema", "wash_average")}
     med_ms = {k: _median(tm.ms(k)) for k in avg_ms}
     selected = int(cnt.item()) / steps
@@ -148,6 +170,7 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
         "momentum": bool(cfg.momentum), "expected_fraction": frac_sel,
         "selected_per_step": selected, "steps": steps,
         "ms_per_step": total_ms / steps, "wall_ms_per_step": wall * 1e3 / steps,
+        "graph_replay_ms_per_step": graph_ms,
         "avg_us": {k: v * 1e3 for k, v in avg_ms.items()},
         "median_us": {k: v * 1e3 for k, v in med_ms.items()},
         "first_steps_us": {k: [round(x * 1e3, 1) for x in tm.ms(k)[:12]] for k in avg_ms},
@@ -297,6 +320,7 @@ def main():
                                f"{'params+momentum' if cfg.momentum else 'params only'}; "
                                "step = wash_shuffle + papa_ema + wash_average",
                    "N": cfg.N, "P": cfg.P, "cache_resident": main_res["cache_resident"]},
+        "graph_replay_ms_per_step": main_res["graph_replay_ms_per_step"],
         "shuffle_coords_per_s": main_res["shuffle_coords_per_s"],
         "selected_per_step": main_res["selected_per_step"],
         "kernel_us": main_res["avg_us"], "kernel_median_us": main_res["median_us"],

@@ -1,0 +1,77 @@
+"""The hot path inside a captured HIP graph: after a first eager call (which builds the cached
+segment table) the entry points only launch kernels on the caller's stream, so a step can be
+captured and replayed.  Every replay is checked against eager execution, with eager work and
+synchronisation between the replays."""
+import numpy as np
+import pytest
+
+import oracle
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def wash():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2405_17517_amd as w
+    return w
+
+
+@pytest.mark.parametrize("stream", ["v1", "gap"])
+def test_step_replays_in_a_graph(wash, stream):
+    shuffle = wash.wash_shuffle if stream == "v1" else wash.wash_shuffle_gap
+    N, P = 5, 300_007
+    rng = np.random.default_rng(0)
+    host = (rng.standard_normal((N, P)) * 0.02).astype(np.float32)
+    segs = wash.SegmentList([(0, P // 2, 0.01), (P // 2, P - P // 2, 0.05)])
+    segs_list = [(0, P // 2, 0.01), (P // 2, P - P // 2, 0.05)]
+
+    pop = torch.from_numpy(host).cuda()
+    mom = pop.clone()
+    cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+    out = torch.empty(P, dtype=torch.float32, device="cuda")
+    dist = torch.empty(N, dtype=torch.float64, device="cuda")
+
+    def step():
+        shuffle(pop, mom, segs, 7, 3, cnt)
+        wash.papa_ema(pop, 0.9)
+        wash.wash_average(pop, out)
+        wash.wash_consensus_sqdist(pop, 0, P, dist)
+
+    # warm-up on a side stream (builds the cached table and the scratch buffer), then capture
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    pop.copy_(torch.from_numpy(host))
+    mom.copy_(torch.from_numpy(host))
+    cnt.zero_()
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    # capture only records: nothing ran yet
+    torch.cuda.synchronize()
+    assert torch.equal(pop.cpu(), torch.from_numpy(host)) and int(cnt.item()) == 0
+
+    ref, refm = host.copy(), host.copy()
+    ref_cnt = 0
+    for replay in range(4):
+        graph.replay()
+        torch.cuda.synchronize()
+        ref_cnt += oracle.shuffle(ref, refm, segs_list, 7, 3, stream=stream)
+        oracle.ema(ref, 0.9)
+        assert np.array_equal(pop.cpu().numpy().view(np.uint32), ref.view(np.uint32)), replay
+        assert np.array_equal(mom.cpu().numpy().view(np.uint32), refm.view(np.uint32)), replay
+        assert int(cnt.item()) == ref_cnt
+        assert np.array_equal(out.cpu().numpy(), oracle.average(ref))
+        assert np.allclose(dist.cpu().numpy(), oracle.consensus_sqdist(ref), rtol=1e-10)
+        # eager work between replays on other buffers must not disturb the graph's state
+        other = torch.from_numpy(host).cuda()
+        shuffle(other, None, segs, 1, replay)
+        wash.wash_average(other)
+        torch.cuda.synchronize()
