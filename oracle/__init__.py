@@ -19,59 +19,69 @@ class Segment(ctypes.Structure):
     _fields_ = [("offset", ctypes.c_uint64), ("length", ctypes.c_uint64), ("p", ctypes.c_double)]
 
 
+def _bind(L):
+    """Declare the argument and result types of every oracle entry point on a loaded library."""
+    u32, u64, dbl = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_double
+    vp = ctypes.c_void_p
+    L.wash_ref_philox4x32_10.argtypes = [vp, vp, vp]
+    L.wash_ref_philox4x32_10.restype = None
+    L.wash_ref_threshold.argtypes = [dbl]
+    L.wash_ref_threshold.restype = u64
+    L.wash_ref_mask_word.argtypes = [u64, u64, u64]
+    L.wash_ref_mask_word.restype = u32
+    L.wash_ref_perm_words.argtypes = [u64, u64, u64, u32, vp]
+    L.wash_ref_perm_words.restype = None
+    L.wash_ref_fisher_yates.argtypes = [vp, u32, vp]
+    L.wash_ref_fisher_yates.restype = None
+    L.wash_ref_permutation.argtypes = [u64, u64, u64, u32, vp]
+    L.wash_ref_permutation.restype = ctypes.c_int
+    L.wash_layer_probs_ref.argtypes = [dbl, u32, ctypes.c_int, vp]
+    L.wash_layer_probs_ref.restype = ctypes.c_int
+    L.wash_shuffle_ref_window.argtypes = [vp, vp, u32, u64, u64, u64, u64, vp, u32, u64, u64, vp]
+    L.wash_shuffle_ref_window.restype = ctypes.c_int
+    L.wash_shuffle_ref.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp]
+    L.wash_shuffle_ref.restype = ctypes.c_int
+    L.wash_shuffle_ref_mt.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp, u32]
+    L.wash_shuffle_ref_mt.restype = ctypes.c_int
+    L.wash_ref_log2.argtypes = [dbl]
+    L.wash_ref_log2.restype = dbl
+    L.wash_ref_gap_scale.argtypes = [dbl]
+    L.wash_ref_gap_scale.restype = dbl
+    L.wash_ref_gap_uniform.argtypes = [u64, u64, u64, u32]
+    L.wash_ref_gap_uniform.restype = u64
+    L.wash_ref_gap.argtypes = [u64, dbl]
+    L.wash_ref_gap.restype = u32
+    L.wash_shuffle_gap_ref_window.argtypes = [vp, vp, u32, u64, u64, u64, u64, vp, u32, u64, u64, vp]
+    L.wash_shuffle_gap_ref_window.restype = ctypes.c_int
+    L.wash_shuffle_gap_ref.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp]
+    L.wash_shuffle_gap_ref.restype = ctypes.c_int
+    L.wash_shuffle_gap_ref_mt.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp, u32]
+    L.wash_shuffle_gap_ref_mt.restype = ctypes.c_int
+    L.wash_ref_gap_mask.argtypes = [vp, u64, vp, u32, u64, u64]
+    L.wash_ref_gap_mask.restype = ctypes.c_int
+    L.wash_consensus_sqdist_ref.argtypes = [vp, u32, u64, u64, u64, vp]
+    L.wash_consensus_sqdist_ref.restype = ctypes.c_int
+    L.wash_weighted_average_ref.argtypes = [vp, vp, vp, u32, u64]
+    L.wash_weighted_average_ref.restype = ctypes.c_int
+    L.wash_average_ref.argtypes = [vp, vp, u32, u64]
+    L.wash_average_ref.restype = ctypes.c_int
+    L.papa_ema_ref.argtypes = [vp, u32, u64, ctypes.c_float]
+    L.papa_ema_ref.restype = ctypes.c_int
+    return L
+
+
 def lib():
     global _LIB
     if _LIB is None:
-        path = _build.build(force=False)
-        L = ctypes.CDLL(path)
-        u32, u64, dbl = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_double
-        vp = ctypes.c_void_p
-        L.wash_ref_philox4x32_10.argtypes = [vp, vp, vp]
-        L.wash_ref_philox4x32_10.restype = None
-        L.wash_ref_threshold.argtypes = [dbl]
-        L.wash_ref_threshold.restype = u64
-        L.wash_ref_mask_word.argtypes = [u64, u64, u64]
-        L.wash_ref_mask_word.restype = u32
-        L.wash_ref_perm_words.argtypes = [u64, u64, u64, u32, vp]
-        L.wash_ref_perm_words.restype = None
-        L.wash_ref_fisher_yates.argtypes = [vp, u32, vp]
-        L.wash_ref_fisher_yates.restype = None
-        L.wash_ref_permutation.argtypes = [u64, u64, u64, u32, vp]
-        L.wash_ref_permutation.restype = ctypes.c_int
-        L.wash_layer_probs_ref.argtypes = [dbl, u32, ctypes.c_int, vp]
-        L.wash_layer_probs_ref.restype = ctypes.c_int
-        L.wash_shuffle_ref_window.argtypes = [vp, vp, u32, u64, u64, u64, u64, vp, u32, u64, u64, vp]
-        L.wash_shuffle_ref_window.restype = ctypes.c_int
-        L.wash_shuffle_ref.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp]
-        L.wash_shuffle_ref.restype = ctypes.c_int
-        L.wash_shuffle_ref_mt.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp, u32]
-        L.wash_shuffle_ref_mt.restype = ctypes.c_int
-        L.wash_ref_log2.argtypes = [dbl]
-        L.wash_ref_log2.restype = dbl
-        L.wash_ref_gap_scale.argtypes = [dbl]
-        L.wash_ref_gap_scale.restype = dbl
-        L.wash_ref_gap_uniform.argtypes = [u64, u64, u64, u32]
-        L.wash_ref_gap_uniform.restype = u64
-        L.wash_ref_gap.argtypes = [u64, dbl]
-        L.wash_ref_gap.restype = u32
-        L.wash_shuffle_gap_ref_window.argtypes = [vp, vp, u32, u64, u64, u64, u64, vp, u32, u64, u64, vp]
-        L.wash_shuffle_gap_ref_window.restype = ctypes.c_int
-        L.wash_shuffle_gap_ref.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp]
-        L.wash_shuffle_gap_ref.restype = ctypes.c_int
-        L.wash_shuffle_gap_ref_mt.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp, u32]
-        L.wash_shuffle_gap_ref_mt.restype = ctypes.c_int
-        L.wash_ref_gap_mask.argtypes = [vp, u64, vp, u32, u64, u64]
-        L.wash_ref_gap_mask.restype = ctypes.c_int
-        L.wash_consensus_sqdist_ref.argtypes = [vp, u32, u64, u64, u64, vp]
-        L.wash_consensus_sqdist_ref.restype = ctypes.c_int
-        L.wash_weighted_average_ref.argtypes = [vp, vp, vp, u32, u64]
-        L.wash_weighted_average_ref.restype = ctypes.c_int
-        L.wash_average_ref.argtypes = [vp, vp, u32, u64]
-        L.wash_average_ref.restype = ctypes.c_int
-        L.papa_ema_ref.argtypes = [vp, u32, u64, ctypes.c_float]
-        L.papa_ema_ref.restype = ctypes.c_int
-        _LIB = L
+        _LIB = _bind(ctypes.CDLL(_build.build(force=False)))
     return _LIB
+
+
+def use_library(path):
+    """Point every wrapper of this module at another build of the oracle (None = the regular
+    one).  For tests that plant a mistake in a copy of the source and check that the pins notice."""
+    global _LIB
+    _LIB = None if path is None else _bind(ctypes.CDLL(path))
 
 
 def _segarray(segs):
