@@ -139,6 +139,8 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
         extra[name] = {"avg_us": ms * 1e3, "alg_bytes": nbytes, "achieved": nbytes / (ms * 1e-3) / 1e9,
                        "frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
+    selected = int(cnt.item()) / steps        # read before the graph replays below add to the counter
+
     # the same step captured once in a HIP graph and replayed (the step number is frozen in the
     # graph, so this is a launch-overhead measurement, not a training loop)
     graph_ms = None
@@ -163,7 +165,6 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
 
     avg_ms = {k: sum(tm.ms(k)) / steps for k in ("wash_shuffle", "papa_ema", "wash_average")}
     med_ms = {k: _median(tm.ms(k)) for k in avg_ms}
-    selected = int(cnt.item()) / steps
     frac_sel = _expected_fraction(segs_list, P)
     res = {
         "config": cfg.index, "name": cfg.name, "stream": stream, "N": N, "P": P, "segments": len(segs_list),
@@ -175,6 +176,7 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
         "median_us": {k: v * 1e3 for k, v in med_ms.items()},
         "first_steps_us": {k: [round(x * 1e3, 1) for x in tm.ms(k)[:12]] for k in avg_ms},
         "shuffle_coords_per_s": P / (avg_ms["wash_shuffle"] * 1e-3),
+        "shuffle_elements_per_s": selected * N * bufs / (avg_ms["wash_shuffle"] * 1e-3),
         "pass_coords_per_s": P / (total_ms / steps * 1e-3),
         "population_bytes": N * P * 4 * bufs,
         "cache_resident": N * P * 4 * bufs <= 256 * (1 << 20),
@@ -200,6 +202,25 @@ def copy_yardstick(torch, wash, n_floats=1 << 28, reps=10):
     ms = a.elapsed_time(b) / reps
     gbs = 2.0 * n_floats * 4 / (ms * 1e-3) / 1e9
     return {"bytes": 2 * n_floats * 4, "avg_us": ms * 1e3, "GBps": gbs, "frac_of_peak": gbs / HBM_PEAK_GBS}
+
+
+def scatter_yardstick(torch, wash, lines=1 << 25, blocks=8192, rounds=16):
+    """G elements/s of independent scattered 4-byte loads, stores and load->store pairs on a 4 GiB buffer:
+    what the memory system gives a sparse shuffle that does nothing but touch its values."""
+    buf = torch.zeros(lines * 32, dtype=torch.float32, device="cuda:0")
+    out = {}
+    for mode, name in ((0, "loads"), (1, "stores"), (2, "load_then_store")):
+        wash.wash_probe_scattered(buf, mode, rounds, blocks)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        n = 0
+        for _ in range(3):
+            n += wash.wash_probe_scattered(buf, mode, rounds, blocks)
+        b.record()
+        torch.cuda.synchronize()
+        out[name + "_Gelem_per_s"] = n / (a.elapsed_time(b) * 1e-3) / 1e9
+    out["buffer_bytes"] = lines * 128
+    return out
 
 
 def cpu_baseline(cfg, budget_s=20.0):
@@ -303,6 +324,7 @@ def main():
     main_res = run_config(torch, wash, cfg, args.steps, args.warmup, p_override=args.p, count=not args.no_count,
                           stream=args.stream)
     yard = copy_yardstick(torch, wash)
+    scat = scatter_yardstick(torch, wash)
 
     roof = main_res["roofline"]
     dominant = max(roof, key=lambda k: roof[k]["avg_us"])
@@ -333,6 +355,8 @@ def main():
                                 for k, v in roof.items()},
         "analysis_passes": main_res["analysis_passes"],
         "copy_yardstick": yard,
+        "scatter_yardstick": scat,
+        "shuffle_elements_per_s": main_res["shuffle_elements_per_s"],
     }
 
     headline_only = args.skip_all_configs or args.config != 2 or args.p is not None or args.stream != "v1"

@@ -188,6 +188,18 @@ int wash_layer_probs(double p, uint32_t L, int schedule, double *out);
  */
 int wash_copy_f32(const float *src, float *dst, uint64_t n, void *stream);
 
+/*
+ * Measurement aid, not part of the method: the yardstick for the shuffle's memory phase.
+ * Every thread of `blocks` x 256 threads does `rounds` rounds of 8 independent 4-byte accesses
+ * to pseudo-random 128-byte lines of buf (mode 0: loads; 1: stores; 2: a load followed by a
+ * store to the same word), i.e. blocks * 256 * rounds * 8 elements per call.  The contents of
+ * buf are overwritten in modes 1 and 2.
+ *   buf    device, lines * 128 bytes       lines  power of two, 2 .. 2^32
+ * Errors: WASH_EINVAL for NULL buf, lines not a power of two, an unknown mode, rounds = 0,
+ * blocks = 0 or > 2^20.
+ */
+int wash_probe_scattered(float *buf, uint64_t lines, int mode, uint32_t rounds, uint32_t blocks, void *stream);
+
 /* Text for a status code (static storage, never NULL). */
 const char *wash_strerror(int status);
 

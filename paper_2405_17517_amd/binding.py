@@ -46,6 +46,8 @@ def _load():
     L.wash_consensus_sqdist.restype = ctypes.c_int
     L.wash_weighted_average.argtypes = [vp, vp, vp, u32, u64, vp]
     L.wash_weighted_average.restype = ctypes.c_int
+    L.wash_probe_scattered.argtypes = [vp, u64, ctypes.c_int, u32, u32, vp]
+    L.wash_probe_scattered.restype = ctypes.c_int
     L.wash_copy_f32.argtypes = [vp, vp, u64, vp]
     L.wash_copy_f32.restype = ctypes.c_int
     L.wash_layer_probs.argtypes = [ctypes.c_double, u32, ctypes.c_int, vp]
@@ -196,6 +198,20 @@ def wash_copy_f32(src: torch.Tensor, dst: torch.Tensor) -> None:
     with torch.cuda.device(src.device):
         rc = _lib.wash_copy_f32(src.data_ptr(), dst.data_ptr(), src.numel(), _stream(src))
     _check(rc, "wash_copy_f32")
+
+
+def wash_probe_scattered(buf: torch.Tensor, mode: int, rounds: int, blocks: int) -> int:
+    """Scattered 4-byte access yardstick on a float32 buffer of a power-of-two number of 128-byte lines
+    (see wash.h); returns the number of elements accessed."""
+    if not (buf.is_cuda and buf.dtype == torch.float32 and buf.is_contiguous()):
+        raise TypeError("need a contiguous float32 GPU tensor")
+    lines = buf.numel() // 32
+    if lines * 32 != buf.numel():
+        raise TypeError("buffer must be a whole number of 128-byte lines")
+    with torch.cuda.device(buf.device):
+        rc = _lib.wash_probe_scattered(buf.data_ptr(), lines, int(mode), int(rounds), int(blocks), _stream(buf))
+    _check(rc, "wash_probe_scattered")
+    return blocks * 256 * rounds * 8
 
 
 def wash_layer_probs(p: float, L: int, schedule: int = 0):

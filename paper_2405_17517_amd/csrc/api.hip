@@ -379,6 +379,22 @@ int wash_copy_f32(const float *src, float *dst, uint64_t n, void *stream)
     return WASH_OK;
 }
 
+int wash_probe_scattered(float *buf, uint64_t lines, int mode, uint32_t rounds, uint32_t blocks, void *stream)
+{
+    g_detail[0] = 0;
+    if (buf == nullptr) return fail(WASH_EINVAL, "buf is NULL");
+    if (lines < 2 || (lines & (lines - 1)) != 0 || lines > (1ull << 32))
+        return fail(WASH_EINVAL, "lines must be a power of two in [2, 2^32]");
+    if (mode < 0 || mode > 2) return fail(WASH_EINVAL, "mode must be 0, 1 or 2");
+    if (rounds == 0 || blocks == 0 || blocks > (1u << 20)) return fail(WASH_EINVAL, "rounds >= 1, 1 <= blocks <= 2^20");
+    // the last word of the buffer takes the (never written) sink of the load-only mode
+    uint32_t *words = reinterpret_cast<uint32_t *>(buf);
+    const hipError_t e = wash::launch_scatter_probe(words, lines, mode, rounds, blocks, words + lines * 32u - 1u,
+                                                    static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip("wash_probe_scattered launch", e);
+    return WASH_OK;
+}
+
 int wash_layer_probs(double p, uint32_t L, int schedule, double *out)
 {
     g_detail[0] = 0;

@@ -132,6 +132,48 @@ __global__ __launch_bounds__(kWave) void sqdist_final_kernel(const double *__res
     if (threadIdx.x == 0) out[n] = v;
 }
 
+// Yardstick for the shuffle: independent 4-byte accesses to pseudo-random 128-byte lines of a
+// large buffer, 8 per thread and round.  mode 0: loads only; 1: stores only; 2: load, then store a
+// value to the same place (the access pattern of a sparse shuffle without any of its arithmetic).
+__device__ __forceinline__ uint32_t probe_mix(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= 0x7FEB352Du;
+    x ^= x >> 15;
+    x *= 0x846CA68Bu;
+    x ^= x >> 16;
+    return x;
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void scatter_probe_kernel(uint32_t *__restrict__ buf, uint32_t line_mask,
+                                                                 uint32_t rounds, uint32_t *__restrict__ sink)
+{
+    constexpr int K = 8;
+    const uint32_t tid = blockIdx.x * kThreads + threadIdx.x;
+    uint32_t acc = tid;
+    for (uint32_t r = 0; r < rounds; ++r) {
+        uint32_t *p[K];
+        uint32_t v[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+            const uint32_t line = probe_mix(tid * 2654435761u + r * 40503u + k * 0x9E3779B9u) & line_mask;
+            p[k] = buf + static_cast<uint64_t>(line) * 32u + (probe_mix(line) & 31u);   // inside line `line`
+        }
+        if (MODE != 1) {
+#pragma unroll
+            for (int k = 0; k < K; ++k) v[k] = __builtin_nontemporal_load(p[k]);
+#pragma unroll
+            for (int k = 0; k < K; ++k) acc ^= v[k];
+        }
+        if (MODE != 0) {
+#pragma unroll
+            for (int k = 0; k < K; ++k) *p[k] = (MODE == 2) ? v[(k + 1) % K] : acc + k;
+        }
+    }
+    if (acc == 0x12345678u) sink[0] = acc;   // keeps the loads alive
+}
+
 template <int N>
 hipError_t run_sqdist(const float *params, uint64_t P, uint64_t g_begin, uint64_t g_end, double *partial,
                       uint32_t nblocks, double *out, hipStream_t stream)
@@ -150,6 +192,21 @@ uint32_t sqdist_blocks(uint64_t span)
 {
     const uint64_t nchunks = (span + kThreads * 4u - 1) / (kThreads * 4u);
     return static_cast<uint32_t>(nchunks < kSqdistMaxBlocks ? (nchunks ? nchunks : 1) : kSqdistMaxBlocks);
+}
+
+hipError_t launch_scatter_probe(uint32_t *buf, uint64_t lines, int mode, uint32_t rounds, uint32_t blocks,
+                                uint32_t *sink, hipStream_t stream)
+{
+    if (lines == 0 || (lines & (lines - 1)) != 0 || lines > (1ull << 32) || blocks == 0 || blocks > (1u << 20))
+        return hipErrorInvalidValue;
+    const uint32_t mask = static_cast<uint32_t>(lines - 1);
+    switch (mode) {
+    case 0: hipLaunchKernelGGL(scatter_probe_kernel<0>, dim3(blocks), dim3(kThreads), 0, stream, buf, mask, rounds, sink); break;
+    case 1: hipLaunchKernelGGL(scatter_probe_kernel<1>, dim3(blocks), dim3(kThreads), 0, stream, buf, mask, rounds, sink); break;
+    case 2: hipLaunchKernelGGL(scatter_probe_kernel<2>, dim3(blocks), dim3(kThreads), 0, stream, buf, mask, rounds, sink); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
 }
 
 hipError_t launch_weighted_average(const float *params, float *out, uint32_t N, uint64_t P, const Weights &w,

@@ -55,6 +55,8 @@ uint32_t sqdist_blocks(uint64_t span);
 hipError_t launch_sqdist(const float *params, uint32_t N, uint64_t P, uint64_t g_begin, uint64_t g_end,
                          double *partial, double *out, hipStream_t stream);
 
+hipError_t launch_scatter_probe(uint32_t *buf, uint64_t lines, int mode, uint32_t rounds, uint32_t blocks,
+                                uint32_t *sink, hipStream_t stream);
 hipError_t launch_copy(const float *src, float *dst, uint64_t n, hipStream_t stream);
 hipError_t launch_ema(float *params, uint32_t N, uint64_t P, float alpha, bool nontemporal, hipStream_t stream);
 
