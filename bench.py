@@ -290,6 +290,7 @@ def main():
     ap.add_argument("--stream-min-bytes", type=int, default=None,
                     help="override the population size from which average/EMA use non-temporal accesses")
     ap.add_argument("--gap-blocks", type=int, default=None, help="override blocks per wavefront of the gap kernel")
+    ap.add_argument("--average-chunks", type=int, default=None, help="chunks per block of wash_average (1, 2, 4, 8)")
     ap.add_argument("--tile-coords", type=int, default=None, help="override the shuffle tile size")
     ap.add_argument("--only", choices=["pass", "copy"], default="pass",
                     help="copy: run only the copy yardstick (for counter calibration)")
@@ -313,6 +314,8 @@ def main():
         wash.wash_set_option(wash.OPT_STREAM_MIN_BYTES, args.stream_min_bytes)
     if args.gap_blocks is not None:
         wash.wash_set_option(wash.OPT_GAP_BLOCKS, args.gap_blocks)
+    if args.average_chunks is not None:
+        wash.wash_set_option(wash.OPT_AVERAGE_CHUNKS, args.average_chunks)
     if args.tile_coords is not None:
         wash.wash_set_option(wash.OPT_TILE_COORDS, args.tile_coords)
 

@@ -216,8 +216,11 @@ const char *wash_last_error_detail(void);
  *                         smaller populations are left to the 256 MB Infinity Cache)
  *   WASH_OPT_GAP_BLOCKS   1024-coordinate blocks walked by one wavefront in wash_shuffle_gap;
  *                         a power of two in [1, 64], or 0 = choose by P and p
+ *   WASH_OPT_AVERAGE_CHUNKS  1024-coordinate chunks owned by one block of wash_average: 1, 2, 4, 8,
+ *                         or 0 = choose by N and P (8 for N >= 10 and P >= 2^26, else 1 or 4)
  */
 #define WASH_OPT_TILE_COORDS 1
+#define WASH_OPT_AVERAGE_CHUNKS 4
 #define WASH_OPT_GAP_BLOCKS 3
 #define WASH_OPT_STREAM_MIN_BYTES 2
 int wash_set_option(int option, int64_t value);

@@ -17,6 +17,7 @@ MAX_N = 32
 OPT_TILE_COORDS = 1
 OPT_STREAM_MIN_BYTES = 2
 OPT_GAP_BLOCKS = 3
+OPT_AVERAGE_CHUNKS = 4
 
 
 class WashError(RuntimeError):

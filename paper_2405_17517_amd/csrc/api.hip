@@ -69,6 +69,7 @@ std::list<Table> g_tables;          // most recently used first
 constexpr size_t kMaxTables = 16;
 int64_t g_tile_coords_option = 0;   // 0 = choose by P
 int64_t g_gap_blocks_option = 0;    // 0 = choose by P
+int64_t g_average_chunks = 0;       // 1024-coordinate chunks per block of wash_average; 0 = choose by P
 int64_t g_stream_min_bytes = 256ll << 20;  // papa_ema on populations at least this large uses non-temporal accesses
 
 uint32_t choose_tile_coords(uint64_t P)
@@ -313,7 +314,8 @@ int wash_average(const float *params, float *out, uint32_t N, uint64_t P, void *
     if (out == nullptr) return fail(WASH_EINVAL, "out is NULL");
     if (ranges_overlap(params, static_cast<uint64_t>(N) * P * sizeof(float), out, P * sizeof(float)))
         return fail(WASH_EINVAL, "out overlaps params");
-    const hipError_t e = wash::launch_average(params, out, N, P, static_cast<hipStream_t>(stream));
+    const int chunks = g_average_chunks != 0 ? static_cast<int>(g_average_chunks) : wash::average_chunks_for(N, P);
+    const hipError_t e = wash::launch_average(params, out, N, P, chunks, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail_hip("wash_average launch", e);
     return WASH_OK;
 }
@@ -442,6 +444,13 @@ int wash_set_option(int option, int64_t value)
             return fail(WASH_EINVAL, "gap blocks per wavefront must be 0 or a power of two in [1, 64]");
         std::lock_guard<std::mutex> lock(g_mutex);
         g_gap_blocks_option = value;
+        return WASH_OK;
+    }
+    if (option == WASH_OPT_AVERAGE_CHUNKS) {
+        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
+            return fail(WASH_EINVAL, "average chunks per block must be 0 (choose by P), 1, 2, 4 or 8");
+        std::lock_guard<std::mutex> lock(g_mutex);
+        g_average_chunks = value;
         return WASH_OK;
     }
     if (option == WASH_OPT_STREAM_MIN_BYTES) {

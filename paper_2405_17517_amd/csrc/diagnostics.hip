@@ -17,36 +17,52 @@ typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
 
 #pragma clang fp contract(off)
 
+// Same shape as the average: a block owns V consecutive chunks of 1024 coordinates and reads the
+// rows one after another (long runs per row keep DRAM pages open), fp64 products and sums in
+// ascending n.
+template <int V>
 __global__ __launch_bounds__(kThreads) void weighted_average_kernel(const float *__restrict__ params,
                                                                     float *__restrict__ out, uint32_t N,
                                                                     uint64_t P, const Weights w)
 {
-    const uint64_t base = (static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4u;
-    if (base >= P) return;
-    if (base + 4u <= P) {
-        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-        const float *src = params + base;
+    constexpr uint64_t kChunk = static_cast<uint64_t>(kThreads) * 4u;
+    const uint64_t first = static_cast<uint64_t>(blockIdx.x) * kChunk * V + threadIdx.x * 4u;
+    double s[V][4];
+#pragma unroll
+    for (int k = 0; k < V; ++k) s[k][0] = s[k][1] = s[k][2] = s[k][3] = 0.0;
+    const float *row = params;
 #pragma unroll 1
-        for (uint32_t n = 0; n < N; ++n) {
-            const f4u v = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(src));
-            src += P;
-            const double wn = w.w[n];
-            s0 += wn * static_cast<double>(v.x);
-            s1 += wn * static_cast<double>(v.y);
-            s2 += wn * static_cast<double>(v.z);
-            s3 += wn * static_cast<double>(v.w);
+    for (uint32_t n = 0; n < N; ++n) {
+        const double wn = w.w[n];
+#pragma unroll
+        for (int k = 0; k < V; ++k) {
+            const uint64_t base = first + k * kChunk;
+            if (base + 4u <= P) {
+                const f4u v = __builtin_nontemporal_load(reinterpret_cast<const f4u *>(row + base));
+                s[k][0] += wn * static_cast<double>(v.x);
+                s[k][1] += wn * static_cast<double>(v.y);
+                s[k][2] += wn * static_cast<double>(v.z);
+                s[k][3] += wn * static_cast<double>(v.w);
+            }
         }
-        f4u o;
-        o.x = static_cast<float>(s0);
-        o.y = static_cast<float>(s1);
-        o.z = static_cast<float>(s2);
-        o.w = static_cast<float>(s3);
-        __builtin_nontemporal_store(o, reinterpret_cast<f4u *>(out + base));
-    } else {
-        for (uint64_t g = base; g < P; ++g) {
-            double s = 0.0;
-            for (uint32_t n = 0; n < N; ++n) s += w.w[n] * static_cast<double>(params[static_cast<uint64_t>(n) * P + g]);
-            out[g] = static_cast<float>(s);
+        row += P;
+    }
+#pragma unroll
+    for (int k = 0; k < V; ++k) {
+        const uint64_t base = first + k * kChunk;
+        if (base + 4u <= P) {
+            f4u o;
+            o.x = static_cast<float>(s[k][0]);
+            o.y = static_cast<float>(s[k][1]);
+            o.z = static_cast<float>(s[k][2]);
+            o.w = static_cast<float>(s[k][3]);
+            __builtin_nontemporal_store(o, reinterpret_cast<f4u *>(out + base));
+        } else if (base < P) {
+            for (uint64_t g = base; g < P; ++g) {
+                double t = 0.0;
+                for (uint32_t n = 0; n < N; ++n) t += w.w[n] * static_cast<double>(params[static_cast<uint64_t>(n) * P + g]);
+                out[g] = static_cast<float>(t);
+            }
         }
     }
 }
@@ -212,11 +228,16 @@ hipError_t launch_scatter_probe(uint32_t *buf, uint64_t lines, int mode, uint32_
 hipError_t launch_weighted_average(const float *params, float *out, uint32_t N, uint64_t P, const Weights &w,
                                    hipStream_t stream)
 {
-    const uint64_t threads = (P + 3u) / 4u;
-    const uint64_t blocks = (threads + kThreads - 1) / kThreads;
+    const int V = average_chunks_for(N, P) >= 4 ? 8 : 1;
+    const uint64_t per_block = static_cast<uint64_t>(kThreads) * 4u * V;
+    const uint64_t blocks = (P + per_block - 1) / per_block;
     if (N == 0 || N > 32 || blocks == 0 || blocks > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL(weighted_average_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, stream, params,
-                       out, N, P, w);
+    if (V == 8)
+        hipLaunchKernelGGL(weighted_average_kernel<8>, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, stream,
+                           params, out, N, P, w);
+    else
+        hipLaunchKernelGGL(weighted_average_kernel<1>, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, stream,
+                           params, out, N, P, w);
     return hipGetLastError();
 }
 
