@@ -8,7 +8,9 @@ workload: one wash_shuffle (thresholds, mask, permutation, gather-permute-
 scatter, plus momentum where the workload has it), one papa_ema (on its own
 copy of the population) and one wash_average.  Inputs are resident in HBM
 before the timed region; timing uses HIP events on the stream the kernels are
-launched on.  One JSON line is printed (see the design doc for the fields).
+launched on.  One JSON line is printed: headline value = coordinates per second of the whole
+pass; per-kernel times, algorithmic bytes and fractions of the 8 TB/s HBM peak; yardsticks (copy,
+scattered access); every config under all_configs; the CPU oracle timed on the same workload.
 """
 import argparse
 import json

@@ -123,6 +123,21 @@ def test_shuffle_consecutive_steps_and_special_values(wash, stream):
     assert np.array_equal(_bits(d.cpu().numpy()), _bits(ref))
 
 
+@pytest.mark.parametrize("stream", STREAMS)
+def test_empty_and_degenerate_inputs(wash, stream):
+    N, P = 32, 5000                                   # the largest population size accepted
+    pop = distinct_population(N, P)
+    for segs in ([], [(0, 0, 0.5)], [(10, 0, 1.0), (10, 0, 1.0)], [(0, P, 0.0)], [(0, 1, 1.0)], [(P - 1, 1, 1.0)],
+                 [(0, 0, 1.0), (0, 3, 1.0), (3, 0, 0.2), (3, 2, 1.0), (4999, 1, 1.0)]):
+        ref = pop.copy()
+        ref_cnt = oracle.shuffle(ref, None, segs, 3, 1, stream=stream)
+        got, _, cnt = _run_shuffle(wash, pop, None, segs, 3, 1, stream=stream)
+        assert cnt == ref_cnt and np.array_equal(_bits(got), _bits(ref)), segs
+    one = distinct_population(1, 300)                 # a single model: nothing can move
+    got, _, cnt = _run_shuffle(wash, one, None, [(0, 300, 1.0)], 3, 1, stream=stream)
+    assert cnt == 300 and np.array_equal(_bits(got), _bits(one))
+
+
 def test_gap_equal_p_neighbours_merge_and_p1_matches_v1(wash):
     N, P = 5, 70_003
     pop = distinct_population(N, P)
