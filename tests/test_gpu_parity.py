@@ -216,3 +216,42 @@ def test_error_paths_launch_nothing(wash):
         wash.wash_average(big)
     torch.cuda.synchronize()
     assert torch.equal(d, keep)
+
+
+def test_table_cache_eviction_shutdown_and_options(wash):
+    # more distinct segment lists than the library caches (16): old tables are freed and rebuilt on demand
+    N, P = 4, 20_000
+    pop = distinct_population(N, P)
+    lists = [[(0, 1000 + 37 * k, 0.3), (5000 + k, 9000, 0.1 + 0.01 * k)] for k in range(20)]
+    expect = []
+    for segs in lists:
+        ref = pop.copy()
+        oracle.shuffle(ref, None, segs, 2, 8)
+        expect.append(ref)
+    for rnd in range(2):
+        for segs, ref in zip(lists, expect):
+            for stream in STREAMS[:1] if rnd else STREAMS:
+                if stream == "v1":
+                    got, _, _ = _run_shuffle(wash, pop, None, segs, 2, 8, stream="v1")
+                    assert np.array_equal(_bits(got), _bits(ref))
+                else:
+                    refg = pop.copy()
+                    oracle.shuffle(refg, None, segs, 2, 8, stream="gap")
+                    got, _, _ = _run_shuffle(wash, pop, None, segs, 2, 8, stream="gap")
+                    assert np.array_equal(_bits(got), _bits(refg))
+    torch.cuda.synchronize()
+    wash.wash_shutdown()                                  # frees every cached table and the scratch buffer
+    got, _, _ = _run_shuffle(wash, pop, None, lists[0], 2, 8)
+    assert np.array_equal(_bits(got), _bits(expect[0]))
+    d = torch.from_numpy(pop).cuda()
+    assert np.allclose(wash.wash_consensus_sqdist(d).cpu().numpy(), oracle.consensus_sqdist(pop), rtol=1e-10)
+    for opt, bad in ((wash.OPT_TILE_COORDS, 100), (wash.OPT_GAP_BLOCKS, 3), (wash.OPT_AVERAGE_CHUNKS, 5),
+                     (wash.OPT_STREAM_MIN_BYTES, -1), (99, 0)):
+        with pytest.raises(wash.WashError):
+            wash.wash_set_option(opt, bad)
+    for opt, vals in ((wash.OPT_GAP_BLOCKS, (1, 64, 0)), (wash.OPT_AVERAGE_CHUNKS, (8, 2, 0)),
+                      (wash.OPT_STREAM_MIN_BYTES, (0, 256 << 20))):
+        for v in vals:
+            wash.wash_set_option(opt, v)
+            avg = wash.wash_average(d).cpu().numpy()
+            assert np.array_equal(avg, oracle.average(pop))
