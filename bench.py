@@ -70,7 +70,7 @@ def kernel_rooflines(N, P, bufs, frac_selected, t_ms):
     return out
 
 
-def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, stream="v1"):
+def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, stream="v1", states=None):
     """Time the hot path on one workload. Returns a dict of measurements."""
     from workloads import device_population
 
@@ -81,6 +81,15 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
     segs = wash.SegmentList(segs_list)
     pop, mom = device_population(tensors, N, cfg.init, cfg.data_seed, cfg.momentum, dev)
     bufs = 2 if cfg.momentum else 1
+    state_bufs = None
+    if states is not None:
+        # WASH+Opt with `states` buffers in all (parameters + optimizer states), through wash_shuffle_states
+        gen = torch.Generator(device=dev).manual_seed(cfg.data_seed + 77)
+        state_bufs = [pop] + ([mom] if mom is not None else [])
+        while len(state_bufs) < states:
+            state_bufs.append(torch.randn(N, P, device=dev, generator=gen) * 1e-3)
+        state_bufs = state_bufs[:states]
+        bufs = states
     big = N * P * 4 > 8 * (1 << 30)
     ema_buf = pop if big else pop.clone()      # EMA works on its own copy unless the population is huge
     out = torch.empty(P, dtype=torch.float32, device=dev)
@@ -92,7 +101,11 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
     shuffle_fn = wash.wash_shuffle if stream == "v1" else wash.wash_shuffle_gap
 
     def do_shuffle():
-        shuffle_fn(pop, mom, segs, cfg.seed, step_no[0], cnt if count else None)
+        if state_bufs is not None:
+            wash.wash_shuffle_states(state_bufs, segs, cfg.seed, step_no[0], gap_stream=(stream == "gap"),
+                                     selected_count=cnt if count else None)
+        else:
+            shuffle_fn(pop, mom, segs, cfg.seed, step_no[0], cnt if count else None)
         step_no[0] += 1
 
     def do_ema():
@@ -170,7 +183,7 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
     frac_sel = _expected_fraction(segs_list, P)
     res = {
         "config": cfg.index, "name": cfg.name, "stream": stream, "N": N, "P": P, "segments": len(segs_list),
-        "momentum": bool(cfg.momentum), "expected_fraction": frac_sel,
+        "momentum": bool(cfg.momentum), "buffers_shuffled": bufs, "expected_fraction": frac_sel,
         "selected_per_step": selected, "steps": steps,
         "ms_per_step": total_ms / steps, "wall_ms_per_step": wall * 1e3 / steps,
         "graph_replay_ms_per_step": graph_ms,
@@ -287,6 +300,8 @@ def main():
                          "is also timed with at most 20 steps each and reported under 'all_configs'")
     ap.add_argument("--stream", choices=["v1", "gap"], default="v1",
                     help="mask stream of the shuffle: v1 = wash_shuffle, gap = wash_shuffle_gap")
+    ap.add_argument("--states", type=int, default=None, choices=[1, 2, 3, 4],
+                    help="shuffle this many buffers (parameters + optimizer states) through wash_shuffle_states")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-count", action="store_true", help="do not ask wash_shuffle for the selected count")
     ap.add_argument("--stream-min-bytes", type=int, default=None,
@@ -327,7 +342,7 @@ def main():
 
     cfg = get_config(args.config)
     main_res = run_config(torch, wash, cfg, args.steps, args.warmup, p_override=args.p, count=not args.no_count,
-                          stream=args.stream)
+                          stream=args.stream, states=args.states)
     yard = copy_yardstick(torch, wash)
     scat = scatter_yardstick(torch, wash)
 
@@ -364,7 +379,7 @@ def main():
         "shuffle_elements_per_s": main_res["shuffle_elements_per_s"],
     }
 
-    headline_only = args.skip_all_configs or args.config != 2 or args.p is not None or args.stream != "v1"
+    headline_only = args.skip_all_configs or args.config != 2 or args.p is not None or args.stream != "v1" or args.states is not None
     if not headline_only or args.all_configs:
         rows = []
         for c in CONFIGS:

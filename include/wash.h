@@ -40,6 +40,7 @@ extern "C" {
 #endif
 
 #define WASH_MAX_N 32u /* largest population size accepted */
+#define WASH_MAX_STATES 4 /* buffers wash_shuffle_states moves together: parameters + 3 optimizer states */
 
 typedef enum wash_status {
     WASH_OK = 0,
@@ -118,6 +119,28 @@ int wash_shuffle_gap(float *params, float *momentum, uint32_t N, uint64_t P,
                      const wash_segment *segs, uint32_t nsegs,
                      uint64_t seed, uint64_t step,
                      uint64_t *selected_count, void *stream);
+
+/*
+ * WASH+Opt (Sec. 3, the variant that also permutes the optimizer state of a
+ * shuffled parameter) for optimizers with more than one state per parameter,
+ * e.g. Adam's two moment estimates: every buffer is permuted with the same mask
+ * and the same permutation per coordinate, in one pass.  wash_shuffle(params,
+ * momentum, ...) is the case nbuffers = 1 or 2 with gap_stream = 0, and
+ * wash_shuffle_gap the same with gap_stream = 1; the result on each buffer is
+ * bit-identical to what those calls give for that buffer alone.
+ *   buffers     HOST array of nbuffers device pointers, each [N, P] fp32 with row
+ *               stride P; buffers[0] is the parameter population; no two may overlap;
+ *               the array is read before the call returns
+ *   nbuffers    1 .. WASH_MAX_STATES
+ *   gap_stream  0: the stream of wash_shuffle; 1: the stream of wash_shuffle_gap
+ *   others      as for wash_shuffle
+ * Errors: as for wash_shuffle, plus WASH_EINVAL for buffers = NULL, a NULL entry,
+ * nbuffers = 0 or > WASH_MAX_STATES, gap_stream not 0 or 1.
+ */
+int wash_shuffle_states(float *const *buffers, uint32_t nbuffers, uint32_t N, uint64_t P,
+                        const wash_segment *segs, uint32_t nsegs,
+                        uint64_t seed, uint64_t step, int gap_stream,
+                        uint64_t *selected_count, void *stream);
 
 /*
  * Uniform average, Alg. 1 output line: out[g] = (1/N) sum_n params[n][g],
@@ -210,7 +233,7 @@ const char *wash_last_error_detail(void);
  * Tuning knobs (process-wide, not part of the method: results never depend
  * on them).  Returns WASH_EINVAL for an unknown option or a value out of range.
  *   WASH_OPT_TILE_COORDS  coordinates scanned by one wavefront in wash_shuffle;
- *                         a multiple of 256 in [256, 65536], or 0 = choose by P
+ *                         a multiple of 256 in [256, 65536], or 0 = choose by P, N and the probabilities
  *   WASH_OPT_STREAM_MIN_BYTES  papa_ema uses non-temporal (cache-bypassing) accesses when the
  *                         population N*P*4 is at least this many bytes (default 256 MiB;
  *                         smaller populations are left to the 256 MB Infinity Cache)

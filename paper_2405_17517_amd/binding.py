@@ -39,6 +39,8 @@ def _load():
     L.wash_shuffle.restype = ctypes.c_int
     L.wash_shuffle_gap.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp, vp]
     L.wash_shuffle_gap.restype = ctypes.c_int
+    L.wash_shuffle_states.argtypes = [vp, u32, u32, u64, vp, u32, u64, u64, ctypes.c_int, vp, vp]
+    L.wash_shuffle_states.restype = ctypes.c_int
     L.wash_average.argtypes = [vp, vp, u32, u64, vp]
     L.wash_average.restype = ctypes.c_int
     L.papa_ema.argtypes = [vp, u32, u64, ctypes.c_float, vp]
@@ -111,6 +113,34 @@ def wash_shuffle_gap(params: torch.Tensor, momentum: Optional[torch.Tensor], seg
     _shuffle(_lib.wash_shuffle_gap, "wash_shuffle_gap", params, momentum, segs, seed, step, selected_count)
 
 
+def wash_shuffle_states(buffers: Sequence[torch.Tensor], segs, seed: int, step: int, gap_stream: bool = False,
+                        selected_count: Optional[torch.Tensor] = None) -> None:
+    """The shuffling step on the parameters (buffers[0]) and every optimizer state at once; see wash.h."""
+    if len(buffers) == 0:
+        raise TypeError("buffers: need at least the parameter population")
+    N, P = _dev_pop(buffers[0], "buffers[0]")
+    for k, b in enumerate(buffers[1:], 1):
+        if _dev_pop(b, f"buffers[{k}]") != (N, P) or b.device != buffers[0].device:
+            raise TypeError(f"buffers[{k}]: shape/device must match buffers[0]")
+    ptrs = (ctypes.c_void_p * len(buffers))(*[b.data_ptr() for b in buffers])
+    cnt_ptr = _count_ptr(selected_count, buffers[0])
+    if not isinstance(segs, SegmentList):
+        segs = SegmentList(segs)
+    with torch.cuda.device(buffers[0].device):
+        rc = _lib.wash_shuffle_states(ctypes.addressof(ptrs), len(buffers), N, P, segs.ptr, segs.n, seed, step,
+                                      1 if gap_stream else 0, cnt_ptr, _stream(buffers[0]))
+    _check(rc, "wash_shuffle_states")
+
+
+def _count_ptr(selected_count, params):
+    if selected_count is None:
+        return None
+    if not (selected_count.is_cuda and selected_count.dtype == torch.int64 and selected_count.numel() == 1
+            and selected_count.device == params.device):
+        raise TypeError("selected_count: need a one-element int64 tensor on the same GPU")
+    return selected_count.data_ptr()
+
+
 def _shuffle(fn, name, params, momentum, segs, seed, step, selected_count) -> None:
     N, P = _dev_pop(params, "params")
     mom_ptr = None
@@ -118,12 +148,7 @@ def _shuffle(fn, name, params, momentum, segs, seed, step, selected_count) -> No
         if _dev_pop(momentum, "momentum") != (N, P) or momentum.device != params.device:
             raise TypeError("momentum: shape/device must match params")
         mom_ptr = momentum.data_ptr()
-    cnt_ptr = None
-    if selected_count is not None:
-        if not (selected_count.is_cuda and selected_count.dtype == torch.int64 and selected_count.numel() == 1
-                and selected_count.device == params.device):
-            raise TypeError("selected_count: need a one-element int64 tensor on the same GPU")
-        cnt_ptr = selected_count.data_ptr()
+    cnt_ptr = _count_ptr(selected_count, params)
     if not isinstance(segs, SegmentList):
         segs = SegmentList(segs)
     with torch.cuda.device(params.device):

@@ -72,10 +72,21 @@ int64_t g_gap_blocks_option = 0;    // 0 = choose by P
 int64_t g_average_chunks = 0;       // 1024-coordinate chunks per block of wash_average; 0 = choose by P
 int64_t g_stream_min_bytes = 256ll << 20;  // papa_ema on populations at least this large uses non-temporal accesses
 
-uint32_t choose_tile_coords(uint64_t P)
+// Coordinates scanned by one wavefront of wash_shuffle.  `moved_per_coord` is the expected number
+// of values moved per coordinate of the row: (selected fraction) * N * (number of buffers).
+uint32_t choose_tile_coords(uint64_t P, double moved_per_coord)
 {
     if (g_tile_coords_option != 0) return static_cast<uint32_t>(g_tile_coords_option);
-    // enough tiles to give each of the 1024 SIMDs several wavefronts, at most 4096 coordinates each
+    // Above about 0.05 values per coordinate the scattered accesses take longer than the mask scan
+    // (measured crossover, N = 20: p between 1e-3 and 3e-3).  Then many short-lived wavefronts with
+    // one batch each do best: the batches of a long tile run one after the other, each waiting
+    // for the stores of the one before (measured, N = 20, P = 87 M, tiles of 512 against 4096:
+    // p = 0.003: 221 / 219 us, 0.01: 715 / 757, 0.03: 1741 / 1977, 0.1: 3201 / 3410; tiles of
+    // 256 lose at p = 0.003: 321 us).
+    if (moved_per_coord >= 0.05) return 512;
+    // The scan dominates: long tiles amortise a wavefront's start-up and its one short batch
+    // (p = 1e-3: 85 us at 4096, 163 us at 512), but keep enough tiles to give each of the 1024
+    // SIMDs several wavefronts.
     uint32_t t = 4096;
     while (t > 256 && (P + t - 1) / t < 8192) t >>= 1;
     return t;
@@ -182,17 +193,26 @@ int check_population(const void *params, uint32_t N, uint64_t P)
 
 extern "C" {
 
-static int shuffle_common(bool gap, float *params, float *momentum, uint32_t N, uint64_t P,
+// bufs[0] is the parameter population, bufs[1 .. nbufs-1] the optimizer states that travel with it
+static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t N, uint64_t P,
                           const wash_segment *segs, uint32_t nsegs, uint64_t seed, uint64_t step,
                           uint64_t *selected_count, void *stream)
 {
     g_detail[0] = 0;
-    if (int rc = check_population(params, N, P)) return rc;
+    static_assert(WASH_MAX_STATES == wash::kMaxBufs, "header and kernel disagree on the number of buffers");
+    if (bufs == nullptr) return fail(WASH_EINVAL, "buffers is NULL");
+    if (nbufs == 0 || nbufs > WASH_MAX_STATES)
+        return fail(WASH_EINVAL, "number of buffers must be in 1..%d, got %u", WASH_MAX_STATES, nbufs);
+    if (int rc = check_population(bufs[0], N, P)) return rc;
     if (step >= (1ull << 32)) return fail(WASH_EINVAL, "step must be < 2^32");
     if (nsegs > 0 && segs == nullptr) return fail(WASH_EINVAL, "segs is NULL");
     const uint64_t pop_bytes = static_cast<uint64_t>(N) * P * sizeof(float);
-    if (momentum != nullptr && ranges_overlap(params, pop_bytes, momentum, pop_bytes))
-        return fail(WASH_EINVAL, "momentum overlaps params");
+    for (uint32_t b = 1; b < nbufs; ++b) {
+        if (bufs[b] == nullptr) return fail(WASH_EINVAL, "buffer %u is NULL", b);
+        for (uint32_t c = 0; c < b; ++c)
+            if (ranges_overlap(bufs[c], pop_bytes, bufs[b], pop_bytes))
+                return fail(WASH_EINVAL, "buffers %u and %u overlap (0 = params, 1 = momentum)", c, b);
+    }
 
     std::vector<wash::DevSegment> active;
     try {
@@ -201,6 +221,7 @@ static int shuffle_common(bool gap, float *params, float *momentum, uint32_t N, 
         return fail(WASH_ENOMEM, "segment list");
     }
     uint64_t prev_end = 0;
+    double expected_selected = 0.0;     // of the default stream: sum of p * length (a launch-shape input only)
     for (uint32_t s = 0; s < nsegs; ++s) {
         const wash_segment &sg = segs[s];
         if (!(sg.p >= 0.0 && sg.p <= 1.0))
@@ -226,6 +247,7 @@ static int shuffle_common(bool gap, float *params, float *momentum, uint32_t N, 
         }
         const uint64_t T = threshold_of(sg.p);
         if (T == 0) continue;                       // never selected: not scanned at all
+        expected_selected += static_cast<double>(T) / 4294967296.0 * static_cast<double>(sg.length);
         wash::DevSegment d{sg.offset, sg.offset + sg.length, T - 1u};
         // neighbours with the same threshold behave as one segment
         if (!active.empty() && active.back().end == d.begin && active.back().param == d.param)
@@ -255,13 +277,14 @@ static int shuffle_common(bool gap, float *params, float *momentum, uint32_t N, 
     if (e != hipSuccess) return fail_hip("hipGetDevice", e);
 
     std::lock_guard<std::mutex> lock(g_mutex);
-    const uint32_t tile_coords = gap ? wash::kGapPiece : choose_tile_coords(P);
+    const uint32_t tile_coords =
+        gap ? wash::kGapPiece : choose_tile_coords(P, expected_selected / static_cast<double>(P) * N * nbufs);
     const Table *table = nullptr;
     if (int rc = get_table(device, P, tile_coords, gap, std::move(active), &table)) return rc;
 
     wash::ShuffleArgs a{};
-    a.params = reinterpret_cast<uint32_t *>(params);
-    a.momentum = reinterpret_cast<uint32_t *>(momentum);
+    for (uint32_t b = 0; b < nbufs; ++b) a.bufs[b] = reinterpret_cast<uint32_t *>(bufs[b]);
+    a.nbufs = nbufs;
     a.N = N;
     a.P = P;
     unsigned char *base = static_cast<unsigned char *>(table->dev);
@@ -297,13 +320,26 @@ static int shuffle_common(bool gap, float *params, float *momentum, uint32_t N, 
 int wash_shuffle(float *params, float *momentum, uint32_t N, uint64_t P, const wash_segment *segs,
                  uint32_t nsegs, uint64_t seed, uint64_t step, uint64_t *selected_count, void *stream)
 {
-    return shuffle_common(false, params, momentum, N, P, segs, nsegs, seed, step, selected_count, stream);
+    float *const bufs[2] = {params, momentum};
+    return shuffle_common(false, bufs, momentum ? 2u : 1u, N, P, segs, nsegs, seed, step, selected_count, stream);
 }
 
 int wash_shuffle_gap(float *params, float *momentum, uint32_t N, uint64_t P, const wash_segment *segs,
                      uint32_t nsegs, uint64_t seed, uint64_t step, uint64_t *selected_count, void *stream)
 {
-    return shuffle_common(true, params, momentum, N, P, segs, nsegs, seed, step, selected_count, stream);
+    float *const bufs[2] = {params, momentum};
+    return shuffle_common(true, bufs, momentum ? 2u : 1u, N, P, segs, nsegs, seed, step, selected_count, stream);
+}
+
+int wash_shuffle_states(float *const *buffers, uint32_t nbuffers, uint32_t N, uint64_t P, const wash_segment *segs,
+                        uint32_t nsegs, uint64_t seed, uint64_t step, int gap_stream, uint64_t *selected_count,
+                        void *stream)
+{
+    if (gap_stream != 0 && gap_stream != 1) {
+        g_detail[0] = 0;
+        return fail(WASH_EINVAL, "gap_stream must be 0 or 1, got %d", gap_stream);
+    }
+    return shuffle_common(gap_stream == 1, buffers, nbuffers, N, P, segs, nsegs, seed, step, selected_count, stream);
 }
 
 

@@ -15,9 +15,11 @@ struct DevSegment {
 
 constexpr uint32_t kNoSegment = 0xFFFFFFFFu;
 
+constexpr uint32_t kMaxBufs = 4;   // parameters + up to three optimizer states
+
 struct ShuffleArgs {
-    uint32_t *params;           // [N, P] as raw 32-bit words
-    uint32_t *momentum;         // [N, P] or nullptr
+    uint32_t *bufs[kMaxBufs];   // each [N, P] as raw 32-bit words: parameters first, then optimizer states
+    uint32_t nbufs;             // 1 .. kMaxBufs
     uint32_t N;
     uint64_t P;
     const DevSegment *segs;     // nsegs active segments, ascending

@@ -59,23 +59,27 @@ __device__ __forceinline__ void gather_row_to_lds(const uint32_t *src, uint32_t 
 }
 
 // Gather, permute and scatter up to 64 queued coordinates, one per lane.
-template <bool kMomentum, typename QueueEntry>
+// kBufs buffers (the parameters, then the optimizer states) share the mask and the permutation;
+// buffer b uses the slab at slab + b * N * 64.
+template <int kBufs, typename QueueEntry>
 __device__ __forceinline__ void permute_batch(const ShuffleArgs &a, uint64_t tile_begin,
-                                              const QueueEntry *queue, uint32_t nbatch,
-                                              uint32_t *slab, uint32_t *slab_m)
+                                              const QueueEntry *queue, uint32_t nbatch, uint32_t *slab)
 {
     const uint32_t lane = lane_id();
     if (lane >= nbatch) return;
     const uint64_t g = tile_begin + queue[lane];
     const uint32_t N = a.N;
     const uint64_t P = a.P;
-    uint32_t *col = a.params + g;
-    uint32_t *col_m = kMomentum ? a.momentum + g : nullptr;
+    const uint32_t slab_words = N * kWave;
+    uint32_t *col[kBufs];
+#pragma unroll
+    for (int b = 0; b < kBufs; ++b) col[b] = a.bufs[b] + g;
 
-    // gather the column(s) into the slab: slab[n][lane]
+    // gather the column(s) into the slab(s): slab[b][n][lane]
     for (uint32_t n = 0; n < N; ++n) {
-        gather_row_to_lds(col + static_cast<uint64_t>(n) * P, slab + n * kWave);
-        if (kMomentum) gather_row_to_lds(col_m + static_cast<uint64_t>(n) * P, slab_m + n * kWave);
+#pragma unroll
+        for (int b = 0; b < kBufs; ++b)
+            gather_row_to_lds(col[b] + static_cast<uint64_t>(n) * P, slab + b * slab_words + n * kWave);
     }
     // While the gathers are in flight, draw the permutation words and reduce them to the swap
     // partners j_i of the descending Fisher-Yates walk (i = N-1 .. 1, j_i = (w * (i+1)) >> 32,
@@ -118,27 +122,25 @@ __device__ __forceinline__ void permute_batch(const ShuffleArgs &a, uint64_t til
             if (i == 0) break;
             const uint32_t j = (pack >> (8u * k)) & 0xFFu;
             const bool write_row = (j != i) || ((moved >> i) & 1u);
-            const uint32_t vi = slab[i * kWave + lane];
-            const uint32_t vj = slab[j * kWave + lane];
-            if (write_row) col[static_cast<uint64_t>(i) * P] = vj;
-            slab[j * kWave + lane] = vi;
-            if (kMomentum) {
-                const uint32_t mi = slab_m[i * kWave + lane];
-                const uint32_t mj = slab_m[j * kWave + lane];
-                if (write_row) col_m[static_cast<uint64_t>(i) * P] = mj;
-                slab_m[j * kWave + lane] = mi;
+#pragma unroll
+            for (int b = 0; b < kBufs; ++b) {
+                uint32_t *sl = slab + b * slab_words;
+                const uint32_t vi = sl[i * kWave + lane];
+                const uint32_t vj = sl[j * kWave + lane];
+                if (write_row) col[b][static_cast<uint64_t>(i) * P] = vj;
+                sl[j * kWave + lane] = vi;
             }
             if (j != i) moved |= 1u << j;
             --i;
         }
     }
     if (moved & 1u) {
-        col[0] = slab[lane];
-        if (kMomentum) col_m[0] = slab_m[lane];
+#pragma unroll
+        for (int b = 0; b < kBufs; ++b) col[b][0] = slab[b * slab_words + lane];
     }
 }
 
-template <bool kMomentum>
+template <int kBufs>
 __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const ShuffleArgs a)
 {
     extern __shared__ uint32_t lds[];
@@ -152,11 +154,10 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
 
     const uint32_t slab_words = a.N * kWave;
     // per wave: [queue: 320 x u16 (tile offsets; a tile has at most 65536 coordinates)][slab(s)]
-    const uint32_t per_wave = kQueueCap / 2 + slab_words * (kMomentum ? 2u : 1u);
+    const uint32_t per_wave = kQueueCap / 2 + slab_words * kBufs;
     uint32_t *base = lds + wave_in_block * per_wave;
     uint16_t *queue = reinterpret_cast<uint16_t *>(base);
     uint32_t *slab = base + kQueueCap / 2;
-    uint32_t *slab_m = slab + slab_words;
 
     const uint64_t tile_begin = tile * a.tile_coords;
     const uint64_t tile_end = min(tile_begin + a.tile_coords, a.P);
@@ -206,7 +207,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
         queued += __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3);
         while (queued >= kWave) {
             wave_lds_sync();
-            permute_batch<kMomentum>(a, tile_begin, queue + (queued - kWave), kWave, slab, slab_m);
+            permute_batch<kBufs>(a, tile_begin, queue + (queued - kWave), kWave, slab);
             queued -= kWave;
             selected += kWave;
             wave_lds_sync();
@@ -214,7 +215,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
     }
     if (queued > 0) {
         wave_lds_sync();
-        permute_batch<kMomentum>(a, tile_begin, queue, queued, slab, slab_m);
+        permute_batch<kBufs>(a, tile_begin, queue, queued, slab);
         selected += queued;
     }
     // One atomic per wavefront on a single address would serialise the whole grid at the
@@ -253,7 +254,7 @@ __global__ __launch_bounds__(kCountSlots) void fold_count_kernel(unsigned long l
 
 constexpr uint32_t kGapQueueCap = 512;       // finds a wavefront can park between two flushes, shared by its lanes
 
-template <bool kMomentum>
+template <int kBufs>
 __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_gap_kernel(const ShuffleArgs a)
 {
     extern __shared__ uint32_t lds[];
@@ -268,12 +269,11 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_gap_kernel(con
     // per wave: [queue: 512 x u16][lists: 512 x u16][slab(s)]; a lane's list holds 512 / blocks_per_wave finds
     const uint32_t list_cap = kGapQueueCap / bpw;
     const uint32_t slab_words = a.N * kWave;
-    const uint32_t per_wave = kGapQueueCap + slab_words * (kMomentum ? 2u : 1u);
+    const uint32_t per_wave = kGapQueueCap + slab_words * kBufs;
     uint32_t *base = lds + wave_in_block * per_wave;
     uint16_t *queue = reinterpret_cast<uint16_t *>(base);
     uint16_t *list = queue + kGapQueueCap + lane * list_cap;
     uint32_t *slab = base + kGapQueueCap;
-    uint32_t *slab_m = slab + slab_words;
     const uint64_t tile_begin = first_block * kGapPiece;
 
     // lane state: the piece [piece_off .. end_off) of its block it is walking, as offsets in the block
@@ -343,8 +343,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_gap_kernel(con
         parked = 0;
         wave_lds_sync();
         for (uint32_t done = 0; done < total; done += kWave) {
-            permute_batch<kMomentum>(a, tile_begin, queue + done, min(total - done, static_cast<uint32_t>(kWave)),
-                                     slab, slab_m);
+            permute_batch<kBufs>(a, tile_begin, queue + done, min(total - done, static_cast<uint32_t>(kWave)), slab);
         }
         selected += total;
         wave_lds_sync();
@@ -359,7 +358,8 @@ hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream)
 {
     if (a.num_tiles == 0 || a.nsegs == 0) return hipSuccess;
     // the direct-to-LDS loads address LDS through a 16-bit offset: keep a block's partition below 64 KiB
-    const size_t per_wave = (kQueueCap / 2 + static_cast<size_t>(a.N) * kWave * (a.momentum ? 2 : 1)) * sizeof(uint32_t);
+    if (a.nbufs == 0 || a.nbufs > kMaxBufs) return hipErrorInvalidValue;
+    const size_t per_wave = (kQueueCap / 2 + static_cast<size_t>(a.N) * kWave * a.nbufs) * sizeof(uint32_t);
     uint32_t waves = kWavesPerBlock;
     while (waves > 1 && per_wave * waves > 65536) waves >>= 1;
     if (per_wave * waves > 65536) return hipErrorInvalidConfiguration;
@@ -367,10 +367,12 @@ hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream)
     if (blocks64 > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
     const dim3 grid(static_cast<uint32_t>(blocks64)), block(kWave * waves);
     const size_t lds_bytes = per_wave * waves;
-    if (a.momentum)
-        hipLaunchKernelGGL(shuffle_kernel<true>, grid, block, lds_bytes, stream, a);
-    else
-        hipLaunchKernelGGL(shuffle_kernel<false>, grid, block, lds_bytes, stream, a);
+    switch (a.nbufs) {
+    case 1: hipLaunchKernelGGL(shuffle_kernel<1>, grid, block, lds_bytes, stream, a); break;
+    case 2: hipLaunchKernelGGL(shuffle_kernel<2>, grid, block, lds_bytes, stream, a); break;
+    case 3: hipLaunchKernelGGL(shuffle_kernel<3>, grid, block, lds_bytes, stream, a); break;
+    default: hipLaunchKernelGGL(shuffle_kernel<4>, grid, block, lds_bytes, stream, a); break;
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.count_slots == nullptr) return e;
     hipLaunchKernelGGL(fold_count_kernel, dim3(1), dim3(kCountSlots), 0, stream, a.count_slots, a.selected_count);
@@ -383,7 +385,8 @@ hipError_t launch_shuffle_gap(const ShuffleArgs &a, hipStream_t stream)
     if (a.blocks_per_wave == 0 || a.blocks_per_wave > kWave || a.tile_coords != kGapPiece)
         return hipErrorInvalidValue;
     if ((a.blocks_per_wave & (a.blocks_per_wave - 1)) != 0) return hipErrorInvalidValue;   // lists share 512 slots evenly
-    const size_t per_wave = (kGapQueueCap + static_cast<size_t>(a.N) * kWave * (a.momentum ? 2 : 1)) * sizeof(uint32_t);
+    if (a.nbufs == 0 || a.nbufs > kMaxBufs) return hipErrorInvalidValue;
+    const size_t per_wave = (kGapQueueCap + static_cast<size_t>(a.N) * kWave * a.nbufs) * sizeof(uint32_t);
     uint32_t waves = kWavesPerBlock;
     while (waves > 1 && per_wave * waves > 65536) waves >>= 1;
     if (per_wave * waves > 65536) return hipErrorInvalidConfiguration;
@@ -391,10 +394,12 @@ hipError_t launch_shuffle_gap(const ShuffleArgs &a, hipStream_t stream)
     const uint64_t blocks64 = (nwaves + waves - 1) / waves;
     if (blocks64 > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
     const dim3 grid(static_cast<uint32_t>(blocks64)), block(kWave * waves);
-    if (a.momentum)
-        hipLaunchKernelGGL(shuffle_gap_kernel<true>, grid, block, per_wave * waves, stream, a);
-    else
-        hipLaunchKernelGGL(shuffle_gap_kernel<false>, grid, block, per_wave * waves, stream, a);
+    switch (a.nbufs) {
+    case 1: hipLaunchKernelGGL(shuffle_gap_kernel<1>, grid, block, per_wave * waves, stream, a); break;
+    case 2: hipLaunchKernelGGL(shuffle_gap_kernel<2>, grid, block, per_wave * waves, stream, a); break;
+    case 3: hipLaunchKernelGGL(shuffle_gap_kernel<3>, grid, block, per_wave * waves, stream, a); break;
+    default: hipLaunchKernelGGL(shuffle_gap_kernel<4>, grid, block, per_wave * waves, stream, a); break;
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.count_slots == nullptr) return e;
     hipLaunchKernelGGL(fold_count_kernel, dim3(1), dim3(kCountSlots), 0, stream, a.count_slots, a.selected_count);

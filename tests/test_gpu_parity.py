@@ -255,3 +255,34 @@ def test_table_cache_eviction_shutdown_and_options(wash):
             wash.wash_set_option(opt, v)
             avg = wash.wash_average(d).cpu().numpy()
             assert np.array_equal(avg, oracle.average(pop))
+
+
+@pytest.mark.parametrize("gap", [False, True])
+@pytest.mark.parametrize("N,P,nbuf", [(2, 1000, 1), (5, 40001, 3), (10, 123457, 4), (20, 65539, 3), (32, 9001, 4),
+                                      (32, 9001, 2), (8, 700_003, 4), (1, 50, 4)])
+def test_shuffle_states_moves_every_buffer_with_one_permutation(wash, N, P, nbuf, gap):
+    # WASH+Opt with several optimizer states (Sec. 3): each buffer ends up as if shuffled alone
+    # with the same (seed, step), because mask and permutation depend on those only
+    print(f"case N={N} P={P} nbuf={nbuf} gap={gap}", flush=True)
+    stream = "gap" if gap else "v1"
+    bufs = [distinct_population(N, P, base=0x3F000000 + k * 0x01000000) for k in range(nbuf)]
+    cut = [0, P // 7, P // 7 + 3, P // 2, P - 1, P]
+    segs = [(cut[k], cut[k + 1] - cut[k], pk) for k, pk in enumerate([0.3, 1.0, 0.004, 0.08, 1.0])]
+    refs, ref_cnt = [], None
+    for b in bufs:
+        r = b.copy()
+        ref_cnt = oracle.shuffle(r, None, segs, 99, 12, stream=stream)
+        refs.append(r)
+    dev = [torch.from_numpy(b).cuda() for b in bufs]
+    cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+    wash.wash_set_option(wash.OPT_TILE_COORDS, 0)
+    wash.wash_shuffle_states(dev, segs, 99, 12, gap_stream=gap, selected_count=cnt)
+    torch.cuda.synchronize()
+    assert int(cnt.item()) == ref_cnt
+    for d, r in zip(dev, refs):
+        assert np.array_equal(_bits(d.cpu().numpy()), _bits(r))
+    if nbuf >= 2:
+        # the two-buffer entry points are the same operation
+        d0, d1 = torch.from_numpy(bufs[0]).cuda(), torch.from_numpy(bufs[1]).cuda()
+        _fn(wash, stream)(d0, d1, segs, 99, 12, None)
+        assert torch.equal(d0, dev[0]) and torch.equal(d1, dev[1])

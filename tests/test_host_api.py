@@ -70,6 +70,20 @@ def test_validation_happens_before_any_gpu_call(lib):
     assert lib.wash_shuffle(4096, None, 2, 0, None, 0, 0, 0, None, None) == -1
     assert lib.wash_shuffle(4096, None, 2, 10, None, 1, 0, 0, None, None) == -1
     assert lib.wash_shuffle(4096, None, 2, 10, None, 0, 0, 0, None, None) == 0      # no segments: nothing to do
+    lib.wash_shuffle_states.argtypes = [vp, u32, u32, u64, vp, u32, u64, u64, ctypes.c_int, vp, vp]
+    lib.wash_last_error_detail.restype = ctypes.c_char_p
+    two = (vp * 2)(4096, 1 << 20)
+    close = (vp * 2)(4096, 4100)
+    hole = (vp * 3)(4096, None, 1 << 20)
+    assert lib.wash_shuffle_states(None, 1, 2, 10, None, 0, 0, 0, 0, None, None) == -1
+    assert lib.wash_shuffle_states(ctypes.addressof(two), 0, 2, 10, None, 0, 0, 0, 0, None, None) == -1
+    assert lib.wash_shuffle_states(ctypes.addressof(two), 5, 2, 10, None, 0, 0, 0, 0, None, None) == -1
+    assert lib.wash_shuffle_states(ctypes.addressof(two), 2, 2, 10, None, 0, 0, 0, 2, None, None) == -1
+    assert lib.wash_shuffle_states(ctypes.addressof(close), 2, 2, 10, None, 0, 0, 0, 0, None, None) == -1
+    assert b"overlap" in lib.wash_last_error_detail()
+    assert lib.wash_shuffle_states(ctypes.addressof(hole), 3, 2, 10, None, 0, 0, 0, 1, None, None) == -1
+    assert lib.wash_shuffle_states(ctypes.addressof(two), 2, 2, 10, None, 0, 0, 1 << 32, 0, None, None) == -1
+    assert lib.wash_shuffle_states(ctypes.addressof(two), 2, 2, 10, None, 0, 0, 0, 1, None, None) == 0   # no segments
     assert lib.wash_average(None, 4096, 2, 10, None) == -1
     assert lib.wash_average(4096, None, 2, 10, None) == -1
     assert lib.wash_average(4096, 4100, 2, 10, None) == -1                          # out overlaps params
