@@ -162,3 +162,83 @@ def test_config5_stress_windows_and_invariants(wash, stream):
         assert not np.array_equal(_bits(got), _bits(ip.cpu().numpy()))
         ref_avg = oracle.average(ref)
         assert _close(avg[g0:g0 + w].cpu().numpy(), ref_avg, np.abs(ref).mean(axis=0)), f"average window {g0}"
+
+
+@pytest.mark.parametrize("stream", STREAMS)
+def test_coordinates_beyond_two_to_the_32(wash, stream):
+    """Rows longer than 2^32 coordinates: the high words of the coordinate enter the Philox counters
+    (permutation words from g = 2^32 on, mask quads through g >> 2).  N = 2 with momentum, 69 GB on
+    the device; compared with the oracle on windows around the 2^32 mark, at both ends, and through
+    the per-coordinate fingerprints over the whole rows."""
+    shuffle = wash.wash_shuffle if stream == "v1" else wash.wash_shuffle_gap
+    N, two32 = 2, 1 << 32
+    P = two32 + (1 << 21) + 5
+    segs_list = [(0, two32 - 1000, 0.0005), (two32 - 1000, 2000 + (1 << 20), 0.5)]
+    rest = segs_list[-1][0] + segs_list[-1][1]
+    segs_list.append((rest, P - rest, 0.01))
+    segs = wash.SegmentList(segs_list)
+
+    def generate(salt):
+        t = torch.empty(N, P, dtype=torch.float32, device="cuda")
+        v = t.view(torch.int32)
+        chunk = 1 << 28
+        for n in range(N):
+            for c0 in range(0, P, chunk):
+                c1 = min(P, c0 + chunk)
+                idx = torch.arange(c0, c1, device="cuda", dtype=torch.int64)
+                # any 32-bit patterns will do (values are moved bit for bit); keep them finite floats
+                v[n, c0:c1] = (((idx * 0x9E3779 + (n + salt) * 0x85EBCA6B) >> 5) & 0x3FFFFFFF).to(torch.int32)
+        return t
+
+    pop, mom = generate(1), generate(11)
+    print("long rows generated", flush=True)
+
+    def fold(t):
+        v = t.view(torch.int32)
+        return v[0] ^ v[1], v[0] + v[1]
+
+    fx, fs = fold(pop)
+    mx, ms = fold(mom)
+    W = 1 << 20
+    starts = [0, two32 - W // 2, two32 + (1 << 20) - 4096, (P - W) // 1024 * 1024, (1 << 31) - 2048, 3 * (1 << 30)]
+    widths = [W if g0 + W + 1024 < P else P - g0 for g0 in starts]
+    init = [(pop[:, g0:g0 + w].clone(), mom[:, g0:g0 + w].clone()) for g0, w in zip(starts, widths)]
+
+    cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+    tiles = [0, 512] if stream == "v1" else [0, 0]
+    for step, tile in enumerate(tiles):
+        wash.wash_set_option(wash.OPT_TILE_COORDS, tile)
+        shuffle(pop, mom, segs, 0xABCDEF0123456789, step, cnt)
+    wash.wash_set_option(wash.OPT_TILE_COORDS, 0)
+    torch.cuda.synchronize()
+    print("long rows shuffled", flush=True)
+
+    gx, gs = fold(pop)
+    assert torch.equal(gx, fx) and torch.equal(gs, fs)
+    del fx, fs, gx, gs
+    gx, gs = fold(mom)
+    assert torch.equal(gx, mx) and torch.equal(gs, ms)
+    del mx, ms, gx, gs
+    steps = len(tiles)
+    mean = steps * sum(length * p for _, length, p in segs_list)
+    var = steps * sum(length * p * (1 - p) for _, length, p in segs_list)
+    assert abs(int(cnt.item()) - mean) < 6 * math.sqrt(var)
+
+    avg = wash.wash_average(pop)
+    refs = []
+    for g0, w, (ip, im) in zip(starts, widths, init):
+        print(f"long rows window at {g0} width {w}", flush=True)
+        ref, refm = ip.cpu().numpy(), im.cpu().numpy()
+        for step in range(steps):
+            oracle.shuffle_window(ref, refm, P, g0, segs_list, 0xABCDEF0123456789, step, stream=stream)
+        assert np.array_equal(_bits(pop[:, g0:g0 + w].contiguous().cpu().numpy()), _bits(ref)), f"params window {g0}"
+        assert np.array_equal(_bits(mom[:, g0:g0 + w].contiguous().cpu().numpy()), _bits(refm)), f"momentum window {g0}"
+        assert not np.array_equal(_bits(ref), _bits(ip.cpu().numpy()))
+        assert _close(avg[g0:g0 + w].cpu().numpy(), oracle.average(ref), np.abs(ref).mean(axis=0)), f"average {g0}"
+        refs.append(ref)
+    # the streaming kernels index rows of more than 2^32 elements as well
+    wash.papa_ema(pop, 0.75)
+    for g0, w, ref in zip(starts, widths, refs):
+        abs_mean = np.abs(ref).mean(axis=0)
+        oracle.ema(ref, 0.75)
+        assert _close(pop[:, g0:g0 + w].contiguous().cpu().numpy(), ref, abs_mean[None, :]), f"EMA window {g0}"
