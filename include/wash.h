@@ -121,7 +121,7 @@ int wash_shuffle_gap(float *params, float *momentum, uint32_t N, uint64_t P,
                      uint64_t *selected_count, void *stream);
 
 /*
- * WASH+Opt (Sec. 3, the variant that also permutes the optimizer state of a
+ * WASH+Opt (Sec. 4, the variant that also permutes the optimizer state of a
  * shuffled parameter) for optimizers with more than one state per parameter,
  * e.g. Adam's two moment estimates: every buffer is permuted with the same mask
  * and the same permutation per coordinate, in one pass.  wash_shuffle(params,

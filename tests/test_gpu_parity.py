@@ -261,7 +261,7 @@ def test_table_cache_eviction_shutdown_and_options(wash):
 @pytest.mark.parametrize("N,P,nbuf", [(2, 1000, 1), (5, 40001, 3), (10, 123457, 4), (20, 65539, 3), (32, 9001, 4),
                                       (32, 9001, 2), (8, 700_003, 4), (1, 50, 4)])
 def test_shuffle_states_moves_every_buffer_with_one_permutation(wash, N, P, nbuf, gap):
-    # WASH+Opt with several optimizer states (Sec. 3): each buffer ends up as if shuffled alone
+    # WASH+Opt with several optimizer states (Sec. 4): each buffer ends up as if shuffled alone
     # with the same (seed, step), because mask and permutation depend on those only
     print(f"case N={N} P={P} nbuf={nbuf} gap={gap}", flush=True)
     stream = "gap" if gap else "v1"
