@@ -377,6 +377,9 @@ def main():
         "copy_yardstick": yard,
         "scatter_yardstick": scat,
         "shuffle_elements_per_s": main_res["shuffle_elements_per_s"],
+        # every moved value needs one scattered store: the measured rate of scattered stores is the shuffle's
+        # practical ceiling where selected coordinates share no cache lines (small p, large population)
+        "shuffle_vs_scattered_stores": main_res["shuffle_elements_per_s"] / (scat["stores_Gelem_per_s"] * 1e9),
     }
 
     headline_only = args.skip_all_configs or args.config != 2 or args.p is not None or args.stream != "v1" or args.states is not None
