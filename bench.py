@@ -34,6 +34,15 @@ def _expected_fraction(segs, P):
     return sum(length * p for _, length, p in segs) / P
 
 
+def _expected_store_units(segs, N, bufs):
+    """Expected number of distinct 64-byte half lines one shuffle launch writes: a half line holds 16
+    coordinates of a row and is written if one of them is selected; of the N rows of a selected
+    coordinate N - 1 change on average (a uniform permutation has one fixed point on average).
+    Scattered stores cost the same per half line whatever their width (measured), so this count over
+    the measured scattered-store rate is the time the memory system needs for the writes alone."""
+    return sum(length / 16.0 * (1.0 - (1.0 - p) ** 16) for _, length, p in segs) * (N - 1) * bufs
+
+
 class Timer:
     """HIP events on the current stream; elapsed() in ms after a synchronize."""
 
@@ -192,6 +201,7 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
         "first_steps_us": {k: [round(x * 1e3, 1) for x in tm.ms(k)[:12]] for k in avg_ms},
         "shuffle_coords_per_s": P / (avg_ms["wash_shuffle"] * 1e-3),
         "shuffle_elements_per_s": selected * N * bufs / (avg_ms["wash_shuffle"] * 1e-3),
+        "shuffle_store_units_per_s": _expected_store_units(segs_list, N, bufs) / (avg_ms["wash_shuffle"] * 1e-3),
         "pass_coords_per_s": P / (total_ms / steps * 1e-3),
         "population_bytes": N * P * 4 * bufs,
         "cache_resident": N * P * 4 * bufs <= 256 * (1 << 20),
@@ -377,9 +387,13 @@ def main():
         "copy_yardstick": yard,
         "scatter_yardstick": scat,
         "shuffle_elements_per_s": main_res["shuffle_elements_per_s"],
-        # every moved value needs one scattered store: the measured rate of scattered stores is the shuffle's
-        # practical ceiling where selected coordinates share no cache lines (small p, large population)
-        "shuffle_vs_scattered_stores": main_res["shuffle_elements_per_s"] / (scat["stores_Gelem_per_s"] * 1e9),
+        # every moved value needs a scattered store: expected distinct 64-byte half lines written per second,
+        # against the measured rate of scattered stores (the shuffle's practical ceiling once the population is
+        # large and p is high enough for the writes to outweigh the mask scan)
+        "shuffle_vs_scattered_stores": {
+            "bound": "scattered-store", "achieved": main_res["shuffle_store_units_per_s"] / 1e9,
+            "peak": scat["stores_Gelem_per_s"], "unit": "G half-lines/s",
+            "frac": main_res["shuffle_store_units_per_s"] / (scat["stores_Gelem_per_s"] * 1e9)},
     }
 
     headline_only = args.skip_all_configs or args.config != 2 or args.p is not None or args.stream != "v1" or args.states is not None
@@ -392,6 +406,8 @@ def main():
                 for st in ("v1", "gap"):
                     res = run_config(torch, wash, c, k, min(args.warmup, 3), p_override=p, stream=st)
                     res["p_override"] = p
+                    res["shuffle_vs_scattered_stores_frac"] = (res["shuffle_store_units_per_s"]
+                                                               / (scat["stores_Gelem_per_s"] * 1e9))
                     rows.append(res)
                     print(f"[bench] config {c.index} p={p} stream {st} done: shuffle "
                           f"{res['avg_us']['wash_shuffle']:.1f} us, ema {res['avg_us']['papa_ema']:.1f} us, "
