@@ -286,3 +286,58 @@ def test_shuffle_states_moves_every_buffer_with_one_permutation(wash, N, P, nbuf
         d0, d1 = torch.from_numpy(bufs[0]).cuda(), torch.from_numpy(bufs[1]).cuda()
         _fn(wash, stream)(d0, d1, segs, 99, 12, None)
         assert torch.equal(d0, dev[0]) and torch.equal(d1, dev[1])
+
+
+def _random_case(rng):
+    N = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 10, 16, 20, 31, 32]))
+    P = int(rng.choice([1, 5, 63, 64, 255, 1023, 1024, 1025, 4097, 20_000, 70_001, 300_007]))
+    nbuf = int(rng.integers(1, 5))
+    gap = bool(rng.integers(0, 2))
+    tile = 0 if gap else int(rng.choice([0, 0, 256, 512, 1280, 4096, 65536]))
+    # a sorted list of non-overlapping segments with holes, empty segments and touching neighbours
+    cuts = np.unique(rng.integers(0, P + 1, size=int(rng.integers(0, 24))))
+    segs, k = [], 0
+    while k + 1 < len(cuts):
+        p = float(rng.choice([0.0, 1.0, 0.5, 0.25, 0.03, 0.004, 1e-4, rng.random()]))
+        segs.append((int(cuts[k]), int(cuts[k + 1] - cuts[k]), p))
+        if rng.random() < 0.2:
+            segs.append((int(cuts[k + 1]), 0, 0.7))          # empty segment
+        k += 1 if rng.random() < 0.7 else 2                   # sometimes leave a hole
+    seed = int(rng.integers(0, 2 ** 63)) * 2 + int(rng.integers(0, 2))
+    step = int(rng.choice([0, 1, 77, 2 ** 31, 2 ** 32 - 1]))
+    return N, P, nbuf, gap, tile, segs, seed, step
+
+
+@pytest.mark.parametrize("case", range(96))
+def test_randomised_shapes_segments_buffers(wash, case):
+    rng = np.random.default_rng(20_000 + case)
+    N, P, nbuf, gap, tile, segs, seed, step = _random_case(rng)
+    print(f"case {case}: N={N} P={P} nbuf={nbuf} gap={gap} tile={tile} nsegs={len(segs)} seed={seed:#x} step={step}",
+          flush=True)
+    stream = "gap" if gap else "v1"
+    bufs = [rng.integers(0, 2 ** 32, size=(N, P), dtype=np.uint64).astype(np.uint32).view(np.float32) for _ in range(nbuf)]
+    refs, ref_cnt = [], 0
+    for b in bufs:
+        r = b.copy()
+        ref_cnt = oracle.shuffle(r, None, segs, seed, step, stream=stream)
+        refs.append(r)
+    dev = [torch.from_numpy(b.copy()).cuda() for b in bufs]
+    cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+    wash.wash_set_option(wash.OPT_TILE_COORDS, tile)
+    try:
+        wash.wash_shuffle_states(dev, segs, seed, step, gap_stream=gap, selected_count=cnt)
+        torch.cuda.synchronize()
+    finally:
+        wash.wash_set_option(wash.OPT_TILE_COORDS, 0)
+    assert int(cnt.item()) == ref_cnt
+    for d, r in zip(dev, refs):
+        assert np.array_equal(_bits(d.cpu().numpy()), _bits(r))
+    # average and EMA of the first buffer's finite stand-in
+    pop = distinct_population(N, P)
+    d = torch.from_numpy(pop).cuda()
+    assert np.array_equal(wash.wash_average(d).cpu().numpy(), oracle.average(pop))
+    alpha = float(rng.choice([0.0, 0.5, 0.99, 1.0]))
+    wash.papa_ema(d, alpha)
+    ref = pop.copy()
+    oracle.ema(ref, alpha)
+    assert np.array_equal(_bits(d.cpu().numpy()), _bits(ref))
