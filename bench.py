@@ -165,13 +165,16 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
 
     selected = int(cnt.item()) / steps        # read before the graph replays below add to the counter
 
-    # the same step captured once in a HIP graph and replayed (the step number is frozen in the
-    # graph, so this is a launch-overhead measurement, not a training loop)
+    # the same step captured once in a HIP graph and replayed; the shuffle reads its step number from
+    # device memory and advances it, so every replay is a new iteration (fresh mask and permutations)
     graph_ms = None
     try:
+        step_dev = torch.full((1,), step_no[0], dtype=torch.int64, device=dev)
+        graph_bufs = state_bufs if state_bufs is not None else ([pop, mom] if mom is not None else [pop])
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
-            do_shuffle()
+            wash.wash_shuffle_device_step(graph_bufs, segs, cfg.seed, step_dev, advance=True,
+                                          gap_stream=(stream == "gap"), selected_count=cnt if count else None)
             do_ema()
             do_avg()
         g.replay()

@@ -143,6 +143,31 @@ int wash_shuffle_states(float *const *buffers, uint32_t nbuffers, uint32_t N, ui
                         uint64_t *selected_count, void *stream);
 
 /*
+ * The shuffling step for callers that replay it from a captured HIP graph.  A
+ * captured launch repeats its arguments, so wash_shuffle in a graph would repeat
+ * one step number and with it one mask and one set of permutations; Alg. 1
+ * draws fresh ones at every iteration.  Here the kernel reads the step number
+ * from device memory when it runs:
+ *   step_dev   device uint64; its value when the kernel runs is the step of that
+ *              launch (the low 32 bits are used: keep it below 2^32); must not
+ *              overlap the buffers
+ *   advance    1: *step_dev is incremented by one after the shuffle, on the same
+ *              stream, so successive launches or replays walk through the steps;
+ *              0: left alone (the caller updates it between replays)
+ *   others     as for wash_shuffle_states
+ * With *step_dev = s the result is bit-identical to wash_shuffle_states with
+ * step = s.  As with the other shuffle entry points, a segment list seen for the
+ * first time builds a device table (allocation + copy): make one call outside the
+ * capture first.
+ * Errors: as for wash_shuffle_states, plus WASH_EINVAL for step_dev = NULL or
+ * advance not 0 or 1.  The value of *step_dev cannot be checked on the host.
+ */
+int wash_shuffle_device_step(float *const *buffers, uint32_t nbuffers, uint32_t N, uint64_t P,
+                             const wash_segment *segs, uint32_t nsegs,
+                             uint64_t seed, uint64_t *step_dev, int advance, int gap_stream,
+                             uint64_t *selected_count, void *stream);
+
+/*
  * Uniform average, Alg. 1 output line: out[g] = (1/N) sum_n params[n][g],
  * summed in fp64 in ascending n and rounded once to fp32.
  *   params  device, [N, P] fp32 (read only)      out  device, [P] fp32, must not overlap params

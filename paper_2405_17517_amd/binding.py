@@ -41,6 +41,8 @@ def _load():
     L.wash_shuffle_gap.restype = ctypes.c_int
     L.wash_shuffle_states.argtypes = [vp, u32, u32, u64, vp, u32, u64, u64, ctypes.c_int, vp, vp]
     L.wash_shuffle_states.restype = ctypes.c_int
+    L.wash_shuffle_device_step.argtypes = [vp, u32, u32, u64, vp, u32, u64, vp, ctypes.c_int, ctypes.c_int, vp, vp]
+    L.wash_shuffle_device_step.restype = ctypes.c_int
     L.wash_average.argtypes = [vp, vp, u32, u64, vp]
     L.wash_average.restype = ctypes.c_int
     L.papa_ema.argtypes = [vp, u32, u64, ctypes.c_float, vp]
@@ -130,6 +132,31 @@ def wash_shuffle_states(buffers: Sequence[torch.Tensor], segs, seed: int, step: 
         rc = _lib.wash_shuffle_states(ctypes.addressof(ptrs), len(buffers), N, P, segs.ptr, segs.n, seed, step,
                                       1 if gap_stream else 0, cnt_ptr, _stream(buffers[0]))
     _check(rc, "wash_shuffle_states")
+
+
+def wash_shuffle_device_step(buffers: Sequence[torch.Tensor], segs, seed: int, step: torch.Tensor,
+                             advance: bool = True, gap_stream: bool = False,
+                             selected_count: Optional[torch.Tensor] = None) -> None:
+    """The shuffling step with the step number read from a one-element int64 device tensor when the kernel runs
+    (and incremented afterwards if `advance`), so that a captured HIP graph walks through the steps; see wash.h."""
+    if len(buffers) == 0:
+        raise TypeError("buffers: need at least the parameter population")
+    N, P = _dev_pop(buffers[0], "buffers[0]")
+    for k, b in enumerate(buffers[1:], 1):
+        if _dev_pop(b, f"buffers[{k}]") != (N, P) or b.device != buffers[0].device:
+            raise TypeError(f"buffers[{k}]: shape/device must match buffers[0]")
+    if not (isinstance(step, torch.Tensor) and step.is_cuda and step.dtype == torch.int64 and step.numel() == 1
+            and step.device == buffers[0].device):
+        raise TypeError("step: need a one-element int64 tensor on the same GPU")
+    ptrs = (ctypes.c_void_p * len(buffers))(*[b.data_ptr() for b in buffers])
+    cnt_ptr = _count_ptr(selected_count, buffers[0])
+    if not isinstance(segs, SegmentList):
+        segs = SegmentList(segs)
+    with torch.cuda.device(buffers[0].device):
+        rc = _lib.wash_shuffle_device_step(ctypes.addressof(ptrs), len(buffers), N, P, segs.ptr, segs.n, seed,
+                                           step.data_ptr(), 1 if advance else 0, 1 if gap_stream else 0, cnt_ptr,
+                                           _stream(buffers[0]))
+    _check(rc, "wash_shuffle_device_step")
 
 
 def _count_ptr(selected_count, params):

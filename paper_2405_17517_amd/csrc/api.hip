@@ -194,9 +194,10 @@ int check_population(const void *params, uint32_t N, uint64_t P)
 extern "C" {
 
 // bufs[0] is the parameter population, bufs[1 .. nbufs-1] the optimizer states that travel with it
+// step_dev != nullptr: the kernel reads the step from device memory (and `advance` asks for *step_dev += 1 afterwards)
 static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t N, uint64_t P,
                           const wash_segment *segs, uint32_t nsegs, uint64_t seed, uint64_t step,
-                          uint64_t *selected_count, void *stream)
+                          uint64_t *selected_count, void *stream, uint64_t *step_dev = nullptr, bool advance = false)
 {
     g_detail[0] = 0;
     static_assert(WASH_MAX_STATES == wash::kMaxBufs, "header and kernel disagree on the number of buffers");
@@ -212,6 +213,12 @@ static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t
         for (uint32_t c = 0; c < b; ++c)
             if (ranges_overlap(bufs[c], pop_bytes, bufs[b], pop_bytes))
                 return fail(WASH_EINVAL, "buffers %u and %u overlap (0 = params, 1 = momentum)", c, b);
+    }
+    if (step_dev != nullptr) {
+        for (uint32_t b = 0; b < nbufs; ++b)
+            if (ranges_overlap(bufs[b], pop_bytes, step_dev, sizeof(uint64_t)))
+                return fail(WASH_EINVAL, "step_dev lies inside buffer %u", b);
+        if (step_dev == selected_count) return fail(WASH_EINVAL, "step_dev and selected_count are the same word");
     }
 
     std::vector<wash::DevSegment> active;
@@ -270,7 +277,14 @@ static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t
         }
         active.resize(kept);
     }
-    if (active.empty()) return WASH_OK;
+    if (active.empty()) {
+        if (step_dev != nullptr && advance) {
+            const hipError_t e0 = wash::launch_step_advance(reinterpret_cast<unsigned long long *>(step_dev),
+                                                            static_cast<hipStream_t>(stream));
+            if (e0 != hipSuccess) return fail_hip("step advance launch", e0);
+        }
+        return WASH_OK;
+    }
 
     int device = 0;
     hipError_t e = hipGetDevice(&device);
@@ -297,6 +311,8 @@ static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t
     a.key_lo = static_cast<uint32_t>(seed);
     a.key_hi = static_cast<uint32_t>(seed >> 32);
     a.step = static_cast<uint32_t>(step);
+    a.step_ptr = reinterpret_cast<const unsigned long long *>(step_dev);
+    a.step_advance = (step_dev != nullptr && advance) ? reinterpret_cast<unsigned long long *>(step_dev) : nullptr;
     a.selected_count = reinterpret_cast<unsigned long long *>(selected_count);
     a.count_slots = selected_count ? reinterpret_cast<unsigned long long *>(base) : nullptr;
     if (gap) {
@@ -342,6 +358,18 @@ int wash_shuffle_states(float *const *buffers, uint32_t nbuffers, uint32_t N, ui
     return shuffle_common(gap_stream == 1, buffers, nbuffers, N, P, segs, nsegs, seed, step, selected_count, stream);
 }
 
+
+int wash_shuffle_device_step(float *const *buffers, uint32_t nbuffers, uint32_t N, uint64_t P,
+                             const wash_segment *segs, uint32_t nsegs, uint64_t seed, uint64_t *step_dev, int advance,
+                             int gap_stream, uint64_t *selected_count, void *stream)
+{
+    g_detail[0] = 0;
+    if (gap_stream != 0 && gap_stream != 1) return fail(WASH_EINVAL, "gap_stream must be 0 or 1, got %d", gap_stream);
+    if (advance != 0 && advance != 1) return fail(WASH_EINVAL, "advance must be 0 or 1, got %d", advance);
+    if (step_dev == nullptr) return fail(WASH_EINVAL, "step_dev is NULL");
+    return shuffle_common(gap_stream == 1, buffers, nbuffers, N, P, segs, nsegs, seed, 0, selected_count, stream,
+                          step_dev, advance == 1);
+}
 
 int wash_average(const float *params, float *out, uint32_t N, uint64_t P, void *stream)
 {

@@ -30,7 +30,9 @@ struct ShuffleArgs {
                                 // gap stream: 1024 (a tile is one restart block; a wavefront walks `blocks_per_wave` of them)
     uint32_t blocks_per_wave;   // gap stream only: 1 .. 64
     uint32_t key_lo, key_hi;    // seed
-    uint32_t step;
+    uint32_t step;              // used when step_ptr is nullptr
+    const unsigned long long *step_ptr; // device step counter read by the kernel (its low 32 bits), or nullptr
+    unsigned long long *step_advance;   // if set, incremented by one after the shuffle (by the kernel that follows it)
     unsigned long long *selected_count; // caller's counter, or nullptr
     unsigned long long *count_slots;    // kCountSlots partial counters, all zero between calls; nullptr iff no counter
 };
@@ -42,6 +44,7 @@ constexpr size_t kCountSlotBytes = static_cast<size_t>(kCountSlots) * kCountSlot
 
 hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream);
 hipError_t launch_shuffle_gap(const ShuffleArgs &a, hipStream_t stream);
+hipError_t launch_step_advance(unsigned long long *step_advance, hipStream_t stream);   // *step_advance += 1
 hipError_t launch_average(const float *params, float *out, uint32_t N, uint64_t P, int chunks_per_block,
                           hipStream_t stream);
 // weights of wash_weighted_average, passed by value as a kernel argument

@@ -47,6 +47,13 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// The step of this launch: a kernel argument, or the low 32 bits of a device counter (so that a
+// captured launch can be replayed with a step that advances).
+__device__ __forceinline__ uint32_t step_of(const ShuffleArgs &a)
+{
+    return a.step_ptr != nullptr ? static_cast<uint32_t>(*a.step_ptr) : a.step;
+}
+
 typedef __attribute__((address_space(1))) const void *global_cptr;
 typedef __attribute__((address_space(3))) void *lds_ptr;
 
@@ -62,7 +69,7 @@ __device__ __forceinline__ void gather_row_to_lds(const uint32_t *src, uint32_t 
 // kBufs buffers (the parameters, then the optimizer states) share the mask and the permutation;
 // buffer b uses the slab at slab + b * N * 64.
 template <int kBufs, typename QueueEntry>
-__device__ __forceinline__ void permute_batch(const ShuffleArgs &a, uint64_t tile_begin,
+__device__ __forceinline__ void permute_batch(const ShuffleArgs &a, uint32_t step, uint64_t tile_begin,
                                               const QueueEntry *queue, uint32_t nbatch, uint32_t *slab)
 {
     const uint32_t lane = lane_id();
@@ -93,7 +100,7 @@ __device__ __forceinline__ void permute_batch(const ShuffleArgs &a, uint64_t til
         // after kMaxCalls rotations the pack of call c sits in ring[c]
         uint32_t pack = 0;
         if (call < ncalls) {
-            const Words4 r = philox4x32_10(g_lo, g_hi, a.step, 1u + call, a.key_lo, a.key_hi);
+            const Words4 r = philox4x32_10(g_lo, g_hi, step, 1u + call, a.key_lo, a.key_hi);
             const uint32_t w[4] = {r.w0, r.w1, r.w2, r.w3};
 #pragma unroll
             for (uint32_t k = 0; k < 4; ++k) {
@@ -151,6 +158,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
     if (tile >= a.num_tiles) return;
     const uint32_t first = a.tile_first[tile];
     if (first == kNoSegment) return;
+    const uint32_t step = step_of(a);
 
     const uint32_t slab_words = a.N * kWave;
     // per wave: [queue: 320 x u16 (tile offsets; a tile has at most 65536 coordinates)][slab(s)]
@@ -173,7 +181,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
         const uint64_t quad = (tile_begin >> 2) + static_cast<uint64_t>(it) * kWave + lane;
         const uint64_t g0 = quad << 2;
         const Words4 r = philox4x32_10(static_cast<uint32_t>(quad), static_cast<uint32_t>(quad >> 32),
-                                       a.step, 0u, a.key_lo, a.key_hi);
+                                       step, 0u, a.key_lo, a.key_hi);
         const uint32_t w[4] = {r.w0, r.w1, r.w2, r.w3};
         bool sel[4];
         if (uniform) {
@@ -207,7 +215,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
         queued += __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3);
         while (queued >= kWave) {
             wave_lds_sync();
-            permute_batch<kBufs>(a, tile_begin, queue + (queued - kWave), kWave, slab);
+            permute_batch<kBufs>(a, step, tile_begin, queue + (queued - kWave), kWave, slab);
             queued -= kWave;
             selected += kWave;
             wave_lds_sync();
@@ -215,7 +223,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
     }
     if (queued > 0) {
         wave_lds_sync();
-        permute_batch<kBufs>(a, tile_begin, queue, queued, slab);
+        permute_batch<kBufs>(a, step, tile_begin, queue, queued, slab);
         selected += queued;
     }
     // One atomic per wavefront on a single address would serialise the whole grid at the
@@ -224,10 +232,15 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
         atomicAdd(a.count_slots + (tile % kCountSlots) * kCountSlotStride, static_cast<unsigned long long>(selected));
 }
 
-// Adds the per-slot partial counts to the caller's counter and clears the slots for the next call.
+// Runs after the shuffle kernel on the same stream.  Adds the per-slot partial counts to the caller's
+// counter and clears the slots for the next call (slots == nullptr: no count was asked for), and
+// advances the device step counter if there is one.
 __global__ __launch_bounds__(kCountSlots) void fold_count_kernel(unsigned long long *slots,
-                                                                 unsigned long long *selected_count)
+                                                                 unsigned long long *selected_count,
+                                                                 unsigned long long *step_advance)
 {
+    if (threadIdx.x == 0 && step_advance != nullptr) *step_advance += 1;
+    if (slots == nullptr) return;
     __shared__ unsigned long long partial[kCountSlots / kWave];
     unsigned long long v = slots[threadIdx.x * kCountSlotStride];
     if (v != 0) slots[threadIdx.x * kCountSlotStride] = 0;
@@ -265,6 +278,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_gap_kernel(con
     const uint32_t bpw = a.blocks_per_wave;
     const uint64_t first_block = wave * bpw;
     if (first_block >= a.num_tiles) return;
+    const uint32_t step = step_of(a);
 
     // per wave: [queue: 512 x u16][lists: 512 x u16][slab(s)]; a lane's list holds 512 / blocks_per_wave finds
     const uint32_t list_cap = kGapQueueCap / bpw;
@@ -302,7 +316,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_gap_kernel(con
         if (active) {
             if ((draw & 1u) == 0) {
                 const uint64_t s = blk_begin + piece_off;
-                r = philox4x32_10(static_cast<uint32_t>(s), static_cast<uint32_t>(s >> 32), a.step,
+                r = philox4x32_10(static_cast<uint32_t>(s), static_cast<uint32_t>(s >> 32), step,
                                   0x80000000u + (draw >> 1), a.key_lo, a.key_hi);
             }
             const uint32_t hi = (draw & 1u) ? r.w2 : r.w0, lo = (draw & 1u) ? r.w3 : r.w1;
@@ -343,7 +357,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_gap_kernel(con
         parked = 0;
         wave_lds_sync();
         for (uint32_t done = 0; done < total; done += kWave) {
-            permute_batch<kBufs>(a, tile_begin, queue + done, min(total - done, static_cast<uint32_t>(kWave)), slab);
+            permute_batch<kBufs>(a, step, tile_begin, queue + done, min(total - done, static_cast<uint32_t>(kWave)), slab);
         }
         selected += total;
         wave_lds_sync();
@@ -354,9 +368,16 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_gap_kernel(con
 
 }  // namespace
 
+hipError_t launch_step_advance(unsigned long long *step_advance, hipStream_t stream)
+{
+    hipLaunchKernelGGL(fold_count_kernel, dim3(1), dim3(kCountSlots), 0, stream,
+                       static_cast<unsigned long long *>(nullptr), static_cast<unsigned long long *>(nullptr), step_advance);
+    return hipGetLastError();
+}
+
 hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream)
 {
-    if (a.num_tiles == 0 || a.nsegs == 0) return hipSuccess;
+    if (a.num_tiles == 0 || a.nsegs == 0) return a.step_advance ? launch_step_advance(a.step_advance, stream) : hipSuccess;
     // the direct-to-LDS loads address LDS through a 16-bit offset: keep a block's partition below 64 KiB
     if (a.nbufs == 0 || a.nbufs > kMaxBufs) return hipErrorInvalidValue;
     const size_t per_wave = (kQueueCap / 2 + static_cast<size_t>(a.N) * kWave * a.nbufs) * sizeof(uint32_t);
@@ -374,14 +395,15 @@ hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream)
     default: hipLaunchKernelGGL(shuffle_kernel<4>, grid, block, lds_bytes, stream, a); break;
     }
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || a.count_slots == nullptr) return e;
-    hipLaunchKernelGGL(fold_count_kernel, dim3(1), dim3(kCountSlots), 0, stream, a.count_slots, a.selected_count);
+    if (e != hipSuccess || (a.count_slots == nullptr && a.step_advance == nullptr)) return e;
+    hipLaunchKernelGGL(fold_count_kernel, dim3(1), dim3(kCountSlots), 0, stream, a.count_slots, a.selected_count,
+                       a.step_advance);
     return hipGetLastError();
 }
 
 hipError_t launch_shuffle_gap(const ShuffleArgs &a, hipStream_t stream)
 {
-    if (a.num_tiles == 0 || a.nsegs == 0) return hipSuccess;
+    if (a.num_tiles == 0 || a.nsegs == 0) return a.step_advance ? launch_step_advance(a.step_advance, stream) : hipSuccess;
     if (a.blocks_per_wave == 0 || a.blocks_per_wave > kWave || a.tile_coords != kGapPiece)
         return hipErrorInvalidValue;
     if ((a.blocks_per_wave & (a.blocks_per_wave - 1)) != 0) return hipErrorInvalidValue;   // lists share 512 slots evenly
@@ -401,8 +423,9 @@ hipError_t launch_shuffle_gap(const ShuffleArgs &a, hipStream_t stream)
     default: hipLaunchKernelGGL(shuffle_gap_kernel<4>, grid, block, per_wave * waves, stream, a); break;
     }
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || a.count_slots == nullptr) return e;
-    hipLaunchKernelGGL(fold_count_kernel, dim3(1), dim3(kCountSlots), 0, stream, a.count_slots, a.selected_count);
+    if (e != hipSuccess || (a.count_slots == nullptr && a.step_advance == nullptr)) return e;
+    hipLaunchKernelGGL(fold_count_kernel, dim3(1), dim3(kCountSlots), 0, stream, a.count_slots, a.selected_count,
+                       a.step_advance);
     return hipGetLastError();
 }
 

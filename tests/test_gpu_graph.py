@@ -75,3 +75,62 @@ def test_step_replays_in_a_graph(wash, stream):
         shuffle(other, None, segs, 1, replay)
         wash.wash_average(other)
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("gap", [False, True])
+def test_device_step_advances_across_replays(wash, gap):
+    """wash_shuffle_device_step reads the step from device memory, so one captured launch replays as
+    successive iterations of Alg. 1: fresh mask and permutations at every replay."""
+    stream = "gap" if gap else "v1"
+    N, P = 6, 200_003
+    rng = np.random.default_rng(5)
+    hosts = [(rng.standard_normal((N, P)) * 0.02).astype(np.float32) for _ in range(3)]
+    segs_list = [(0, P // 3, 0.02), (P // 3, P - P // 3 - 1000, 0.004)]
+    segs = wash.SegmentList(segs_list)
+    empty = wash.SegmentList([(10, 100, 0.0)])
+    bufs = [torch.from_numpy(h).cuda() for h in hosts]
+    step = torch.full((1,), 40, dtype=torch.int64, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+
+    # eager: step taken from the device word, advanced afterwards; with advance=False it stays
+    refs = [h.copy() for h in hosts]
+    ref_cnt = 0
+    wash.wash_shuffle_device_step(bufs, segs, 9, step, advance=False, gap_stream=gap, selected_count=cnt)
+    wash.wash_shuffle_device_step(bufs, segs, 9, step, advance=True, gap_stream=gap, selected_count=cnt)
+    wash.wash_shuffle_device_step(bufs, empty, 9, step, advance=True, gap_stream=gap)     # nothing to shuffle: still advances
+    torch.cuda.synchronize()
+    assert int(step.item()) == 42
+    for s_ in (40, 40):
+        for r in refs:
+            c = oracle.shuffle(r, None, segs_list, 9, s_, stream=stream)
+        ref_cnt += c
+    assert int(cnt.item()) == ref_cnt
+    for b, r in zip(bufs, refs):
+        assert np.array_equal(b.cpu().numpy().view(np.uint32), r.view(np.uint32))
+
+    # captured once, replayed five times: steps 42 .. 46
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        wash.wash_shuffle_device_step(bufs, segs, 9, step, advance=True, gap_stream=gap, selected_count=cnt)
+    torch.cuda.synchronize()
+    assert int(step.item()) == 42
+    for replay in range(5):
+        graph.replay()
+        torch.cuda.synchronize()
+        for r in refs:
+            c = oracle.shuffle(r, None, segs_list, 9, 42 + replay, stream=stream)
+        ref_cnt += c
+        assert int(step.item()) == 43 + replay
+        assert int(cnt.item()) == ref_cnt
+        for b, r in zip(bufs, refs):
+            assert np.array_equal(b.cpu().numpy().view(np.uint32), r.view(np.uint32)), replay
+        other = torch.from_numpy(hosts[0]).cuda()                 # eager work between replays
+        wash.wash_shuffle(other, None, segs, 1, replay)
+        torch.cuda.synchronize()
+    # the two-buffer entry point at the same step gives the same bits
+    a, b = torch.from_numpy(hosts[0]).cuda(), torch.from_numpy(hosts[1]).cuda()
+    c, d = a.clone(), b.clone()
+    step.fill_(1234)
+    wash.wash_shuffle_device_step([a, b], segs, 3, step, advance=False, gap_stream=gap)
+    (wash.wash_shuffle_gap if gap else wash.wash_shuffle)(c, d, segs, 3, 1234)
+    assert torch.equal(a, c) and torch.equal(b, d)

@@ -84,6 +84,15 @@ def test_validation_happens_before_any_gpu_call(lib):
     assert lib.wash_shuffle_states(ctypes.addressof(hole), 3, 2, 10, None, 0, 0, 0, 1, None, None) == -1
     assert lib.wash_shuffle_states(ctypes.addressof(two), 2, 2, 10, None, 0, 0, 1 << 32, 0, None, None) == -1
     assert lib.wash_shuffle_states(ctypes.addressof(two), 2, 2, 10, None, 0, 0, 0, 1, None, None) == 0   # no segments
+    lib.wash_shuffle_device_step.argtypes = [vp, u32, u32, u64, vp, u32, u64, vp, ctypes.c_int, ctypes.c_int, vp, vp]
+    far = 1 << 30
+    assert lib.wash_shuffle_device_step(ctypes.addressof(two), 2, 2, 10, None, 0, 0, None, 1, 0, None, None) == -1
+    assert lib.wash_shuffle_device_step(ctypes.addressof(two), 2, 2, 10, None, 0, 0, far, 2, 0, None, None) == -1
+    assert lib.wash_shuffle_device_step(ctypes.addressof(two), 2, 2, 10, None, 0, 0, far, 1, 3, None, None) == -1
+    assert lib.wash_shuffle_device_step(ctypes.addressof(two), 2, 2, 10, None, 0, 0, 4096 + 8, 1, 0, None, None) == -1
+    assert b"step_dev" in lib.wash_last_error_detail()
+    assert lib.wash_shuffle_device_step(ctypes.addressof(two), 2, 2, 10, None, 0, 0, far, 1, 0, far, None) == -1
+    assert lib.wash_shuffle_device_step(ctypes.addressof(two), 5, 2, 10, None, 0, 0, far, 1, 0, None, None) == -1
     assert lib.wash_average(None, 4096, 2, 10, None) == -1
     assert lib.wash_average(4096, None, 2, 10, None) == -1
     assert lib.wash_average(4096, 4100, 2, 10, None) == -1                          # out overlaps params
