@@ -74,3 +74,25 @@ def test_product_and_oracle_do_not_touch_each_other():
     for path in _python_sources("workloads"):
         text = open(path).read()
         assert not re.search(r"^\s*(from|import)\s+(oracle|paper_2405_17517_amd)\b", text, re.M), path
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode != 0
+    assert "ONE GPU" in res.stderr + res.stdout
+
+
+def test_bench_store_unit_model():
+    # expected distinct 64-byte half lines written by one shuffle launch: closed-form corner cases
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(ROOT, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    units = bench._expected_store_units
+    assert units([(0, 1600, 1.0)], 4, 1) == 100 * 3            # every half line of N - 1 rows
+    assert units([(0, 1600, 0.0)], 4, 2) == 0
+    small = units([(0, 16_000_000, 1e-6)], 2, 1)               # rare selections never share a half line
+    assert abs(small - 16.0) < 1e-3
+    assert abs(units([(0, 160, 0.5), (160, 160, 0.5)], 3, 2) - 2 * units([(0, 160, 0.5)], 3, 2)) < 1e-12
