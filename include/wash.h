@@ -158,7 +158,9 @@ int wash_shuffle_states(float *const *buffers, uint32_t nbuffers, uint32_t N, ui
  * With *step_dev = s the result is bit-identical to wash_shuffle_states with
  * step = s.  As with the other shuffle entry points, a segment list seen for the
  * first time builds a device table (allocation + copy): make one call outside the
- * capture first.
+ * capture first.  A table that a capturing stream has used is kept until
+ * wash_shutdown (replays read it), whatever other segment lists come later; call
+ * wash_shutdown only once no graph that contains a shuffle will be replayed again.
  * Errors: as for wash_shuffle_states, plus WASH_EINVAL for step_dev = NULL or
  * advance not 0 or 1.  The value of *step_dev cannot be checked on the host.
  */

@@ -62,6 +62,7 @@ struct Table {
     TableKey key;
     void *dev = nullptr;            // [count slots][DevSegment x nsegs][uint32 x num_tiles]
     uint64_t num_tiles = 0;
+    bool pinned = false;            // recorded into a captured graph: kept until wash_shutdown
 };
 
 std::mutex g_mutex;
@@ -94,7 +95,7 @@ uint32_t choose_tile_coords(uint64_t P, double moved_per_coord)
 
 // Builds (or finds) the device table for this call; on success *out points at the cached entry.
 int get_table(int device, uint64_t P, uint32_t tile_coords, bool gap, std::vector<wash::DevSegment> &&active,
-              const Table **out)
+              Table **out)
 {
     TableKey key{device, P, tile_coords, gap ? 1 : 0, std::move(active)};
     for (auto it = g_tables.begin(); it != g_tables.end(); ++it) {
@@ -125,11 +126,17 @@ int get_table(int device, uint64_t P, uint32_t tile_coords, bool gap, std::vecto
         tile_first[t] = (s < nsegs && key.segs[s].begin < end) ? static_cast<uint32_t>(s) : wash::kNoSegment;
     }
     if (g_tables.size() >= kMaxTables) {
-        // hipFree waits for the device, so no launched kernel still reads the table
-        (void)hipSetDevice(g_tables.back().key.device);
-        (void)hipFree(g_tables.back().dev);
-        (void)hipSetDevice(device);
-        g_tables.pop_back();
+        // drop the least recently used table that no captured graph refers to (if every table is
+        // pinned the cache grows); hipFree waits for the device, so no launched kernel still reads it
+        for (auto it = g_tables.end(); it != g_tables.begin();) {
+            --it;
+            if (it->pinned) continue;
+            (void)hipSetDevice(it->key.device);
+            (void)hipFree(it->dev);
+            (void)hipSetDevice(device);
+            g_tables.erase(it);
+            break;
+        }
     }
     void *dev = nullptr;
     hipError_t e = hipMalloc(&dev, bytes);
@@ -293,8 +300,16 @@ static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t
     std::lock_guard<std::mutex> lock(g_mutex);
     const uint32_t tile_coords =
         gap ? wash::kGapPiece : choose_tile_coords(P, expected_selected / static_cast<double>(P) * N * nbufs);
-    const Table *table = nullptr;
+    Table *table = nullptr;
     if (int rc = get_table(device, P, tile_coords, gap, std::move(active), &table)) return rc;
+    // A launch recorded into a graph keeps using this table at every replay: never evict it.
+    if (stream != nullptr) {
+        hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(static_cast<hipStream_t>(stream), &capture) != hipSuccess)
+            (void)hipGetLastError();
+        else if (capture == hipStreamCaptureStatusActive)
+            table->pinned = true;
+    }
 
     wash::ShuffleArgs a{};
     for (uint32_t b = 0; b < nbufs; ++b) a.bufs[b] = reinterpret_cast<uint32_t *>(bufs[b]);

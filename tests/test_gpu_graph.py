@@ -134,3 +134,31 @@ def test_device_step_advances_across_replays(wash, gap):
     wash.wash_shuffle_device_step([a, b], segs, 3, step, advance=False, gap_stream=gap)
     (wash.wash_shuffle_gap if gap else wash.wash_shuffle)(c, d, segs, 3, 1234)
     assert torch.equal(a, c) and torch.equal(b, d)
+
+
+def test_table_of_a_captured_launch_survives_cache_eviction(wash):
+    # the library caches 16 segment tables; a table that a captured launch refers to must outlive
+    # any number of later segment lists, because every replay reads it again
+    N, P = 4, 50_021
+    rng = np.random.default_rng(9)
+    host = (rng.standard_normal((N, P)) * 0.02).astype(np.float32)
+    segs_list = [(3, 20_000, 0.05), (25_000, 25_000, 0.01)]
+    segs = wash.SegmentList(segs_list)
+    pop = torch.from_numpy(host).cuda()
+    step = torch.zeros(1, dtype=torch.int64, device="cuda")
+    wash.wash_shuffle_device_step([pop], segs, 2, step, advance=False)      # builds the table outside the capture
+    torch.cuda.synchronize()
+    pop.copy_(torch.from_numpy(host))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        wash.wash_shuffle_device_step([pop], segs, 2, step, advance=True)
+    ref = host.copy()
+    for replay in range(3):
+        other = torch.from_numpy(host).cuda()
+        for k in range(20):                                                  # 20 new lists: evicts every unpinned table
+            wash.wash_shuffle(other, None, [(k + 1 + 100 * replay, 1000 + k, 0.1)], 0, 0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        oracle.shuffle(ref, None, segs_list, 2, replay)
+        assert np.array_equal(pop.cpu().numpy().view(np.uint32), ref.view(np.uint32)), replay
