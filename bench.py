@@ -322,6 +322,8 @@ def main():
     ap.add_argument("--gap-blocks", type=int, default=None, help="override blocks per wavefront of the gap kernel")
     ap.add_argument("--average-chunks", type=int, default=None, help="chunks per block of wash_average (1, 2, 4, 8)")
     ap.add_argument("--tile-coords", type=int, default=None, help="override the shuffle tile size")
+    ap.add_argument("--dense", type=int, default=None, choices=[0, 1, 2],
+                    help="wash_shuffle's dense path: 0 automatic, 1 never, 2 whenever it fits")
     ap.add_argument("--only", choices=["pass", "copy"], default="pass",
                     help="copy: run only the copy yardstick (for counter calibration)")
     args = ap.parse_args()
@@ -348,6 +350,8 @@ def main():
         wash.wash_set_option(wash.OPT_AVERAGE_CHUNKS, args.average_chunks)
     if args.tile_coords is not None:
         wash.wash_set_option(wash.OPT_TILE_COORDS, args.tile_coords)
+    if args.dense is not None:
+        wash.wash_set_option(wash.OPT_DENSE, args.dense)
 
     if args.only == "copy":
         print(json.dumps({"copy_yardstick": copy_yardstick(torch, wash)}))

@@ -84,7 +84,11 @@ typedef struct wash_segment {
  *   P               coordinates per model, >= 1
  *   segs            HOST array of nsegs segments, sorted by offset and not
  *                   overlapping; read before the call returns.  Coordinates in
- *                   no segment are never shuffled.
+ *                   no segment are never shuffled.  (When every segment has
+ *                   p >= 0.08 the rows are streamed through on-chip memory in
+ *                   strips of 256 coordinates, and the call may then rewrite
+ *                   any element of such a strip with the value it already has;
+ *                   see WASH_OPT_DENSE.)
  *   nsegs           number of segments (0 allowed: nothing happens)
  *   seed, step      stream address; step < 2^32
  *   selected_count  device uint64 or NULL; the number of selected coordinates
@@ -268,11 +272,16 @@ const char *wash_last_error_detail(void);
  *                         a power of two in [1, 64], or 0 = choose by P and p
  *   WASH_OPT_AVERAGE_CHUNKS  1024-coordinate chunks owned by one block of wash_average: 1, 2, 4, 8,
  *                         or 0 = choose by N and P (8 for N >= 10 and P >= 2^26, else 1 or 4)
+ *   WASH_OPT_DENSE        wash_shuffle has a second code path that streams whole rows through
+ *                         on-chip memory instead of gathering single values (same results);
+ *                         0 = use it when every segment's probability is high enough for it
+ *                         to be faster, 1 = never, 2 = whenever N * buffers <= 63
  */
 #define WASH_OPT_TILE_COORDS 1
 #define WASH_OPT_AVERAGE_CHUNKS 4
 #define WASH_OPT_GAP_BLOCKS 3
 #define WASH_OPT_STREAM_MIN_BYTES 2
+#define WASH_OPT_DENSE 5
 int wash_set_option(int option, int64_t value);
 
 /* Free the cached device tables of every device (waits for the devices). */

@@ -18,6 +18,7 @@ OPT_TILE_COORDS = 1
 OPT_STREAM_MIN_BYTES = 2
 OPT_GAP_BLOCKS = 3
 OPT_AVERAGE_CHUNKS = 4
+OPT_DENSE = 5
 
 
 class WashError(RuntimeError):

@@ -71,6 +71,7 @@ constexpr size_t kMaxTables = 16;
 int64_t g_tile_coords_option = 0;   // 0 = choose by P
 int64_t g_gap_blocks_option = 0;    // 0 = choose by P
 int64_t g_average_chunks = 0;       // 1024-coordinate chunks per block of wash_average; 0 = choose by P
+int64_t g_dense_option = 0;         // wash_shuffle's dense path: 0 = by probability, 1 = never, 2 = whenever it fits
 int64_t g_stream_min_bytes = 256ll << 20;  // papa_ema on populations at least this large uses non-temporal accesses
 
 // Coordinates scanned by one wavefront of wash_shuffle.  `moved_per_coord` is the expected number
@@ -236,6 +237,7 @@ static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t
     }
     uint64_t prev_end = 0;
     double expected_selected = 0.0;     // of the default stream: sum of p * length (a launch-shape input only)
+    uint64_t min_threshold = 1ull << 32; // smallest threshold of an active segment of the default stream
     for (uint32_t s = 0; s < nsegs; ++s) {
         const wash_segment &sg = segs[s];
         if (!(sg.p >= 0.0 && sg.p <= 1.0))
@@ -262,6 +264,7 @@ static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t
         const uint64_t T = threshold_of(sg.p);
         if (T == 0) continue;                       // never selected: not scanned at all
         expected_selected += static_cast<double>(T) / 4294967296.0 * static_cast<double>(sg.length);
+        if (T < min_threshold) min_threshold = T;
         wash::DevSegment d{sg.offset, sg.offset + sg.length, T - 1u};
         // neighbours with the same threshold behave as one segment
         if (!active.empty() && active.back().end == d.begin && active.back().param == d.param)
@@ -298,8 +301,17 @@ static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t
     if (e != hipSuccess) return fail_hip("hipGetDevice", e);
 
     std::lock_guard<std::mutex> lock(g_mutex);
+    // Dense path of the default stream: streaming a 256-coordinate strip of all rows through LDS costs the same
+    // whatever p is, the sparse path's scattered accesses grow with p until every half line is touched.
+    // Measured crossover at p = 0.08 (N = 20, P = 87 M: dense 2.92 ms; sparse 2.38 ms at p = 0.05, 2.79 at 0.07,
+    // 3.20 at 0.1, 3.57 from 0.25 on.  N = 10, P = 26 M, two buffers: dense 0.82-0.86 ms; sparse 0.68 at 0.05,
+    // 0.91 at 0.1, 1.03 at 1).  It is used when every active segment is at least that dense.
+    const bool dense_fits = N >= 2 && wash::shuffle_dense_lds_bytes(N, nbufs) <= 65536;
+    const bool dense = !gap && dense_fits && g_tile_coords_option == 0 &&
+                       (g_dense_option == 2 || (g_dense_option == 0 && min_threshold >= threshold_of(0.08)));
     const uint32_t tile_coords =
-        gap ? wash::kGapPiece : choose_tile_coords(P, expected_selected / static_cast<double>(P) * N * nbufs);
+        gap ? wash::kGapPiece
+            : dense ? 256u : choose_tile_coords(P, expected_selected / static_cast<double>(P) * N * nbufs);
     Table *table = nullptr;
     if (int rc = get_table(device, P, tile_coords, gap, std::move(active), &table)) return rc;
     // A launch recorded into a graph keeps using this table at every replay: never evict it.
@@ -341,6 +353,9 @@ static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t
         if (g_gap_blocks_option != 0) bpw = static_cast<uint32_t>(g_gap_blocks_option);
         a.blocks_per_wave = bpw;
         e = wash::launch_shuffle_gap(a, static_cast<hipStream_t>(stream));
+    } else if (dense) {
+        a.dense_nontemporal = pop_bytes * nbufs >= (4ull << 30) ? 1u : 0u;
+        e = wash::launch_shuffle_dense(a, static_cast<hipStream_t>(stream));
     } else {
         e = wash::launch_shuffle(a, static_cast<hipStream_t>(stream));
     }
@@ -530,6 +545,12 @@ int wash_set_option(int option, int64_t value)
             return fail(WASH_EINVAL, "average chunks per block must be 0 (choose by P), 1, 2, 4 or 8");
         std::lock_guard<std::mutex> lock(g_mutex);
         g_average_chunks = value;
+        return WASH_OK;
+    }
+    if (option == WASH_OPT_DENSE) {
+        if (value < 0 || value > 2) return fail(WASH_EINVAL, "dense path option must be 0 (automatic), 1 (never) or 2 (always)");
+        std::lock_guard<std::mutex> lock(g_mutex);
+        g_dense_option = value;
         return WASH_OK;
     }
     if (option == WASH_OPT_STREAM_MIN_BYTES) {

@@ -65,6 +65,43 @@ __device__ __forceinline__ void gather_row_to_lds(const uint32_t *src, uint32_t 
     __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)row, 4, 0, 0);
 }
 
+// The same for data that is read once and written once (the dense path): non-temporal, like the
+// streaming kernels of this library.
+__device__ __forceinline__ void stream_row_to_lds(const uint32_t *src, uint32_t *row)
+{
+    __builtin_amdgcn_global_load_lds((global_cptr)src, (lds_ptr)row, 4, 0, 2);   // aux bit 1: nt
+}
+
+// The swap partners j_i of the descending Fisher-Yates walk of coordinate g (i = N-1 .. 1,
+// j_i = (w * (i+1)) >> 32 with the permutation words w of the stream, four per Philox call), packed
+// one byte each, four to a register.  The packs sit in a register ring that is rotated instead of
+// indexed, so the loops stay rolled: after the kMaxCalls rotations below the pack of call c is in ring[c].
+__device__ __forceinline__ void draw_swap_partners(const ShuffleArgs &a, uint32_t step, uint64_t g,
+                                                   uint32_t (&ring)[kMaxCalls])
+{
+    const uint32_t N = a.N;
+    const uint32_t g_lo = static_cast<uint32_t>(g), g_hi = static_cast<uint32_t>(g >> 32);
+    const uint32_t nswaps = N - 1;
+    const uint32_t ncalls = (nswaps + 3u) / 4u;             // <= kMaxCalls
+#pragma unroll
+    for (uint32_t q = 0; q < kMaxCalls; ++q) ring[q] = 0;
+    for (uint32_t call = 0; call < kMaxCalls; ++call) {
+        uint32_t pack = 0;
+        if (call < ncalls) {
+            const Words4 r = philox4x32_10(g_lo, g_hi, step, 1u + call, a.key_lo, a.key_hi);
+            const uint32_t w[4] = {r.w0, r.w1, r.w2, r.w3};
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k) {
+                const uint32_t t = call * 4u + k;
+                if (t < nswaps) pack |= __umulhi(w[k], N - t) << (8u * k);   // i + 1 = N - t
+            }
+        }
+#pragma unroll
+        for (uint32_t q = 0; q + 1 < kMaxCalls; ++q) ring[q] = ring[q + 1];
+        ring[kMaxCalls - 1] = pack;
+    }
+}
+
 // Gather, permute and scatter up to 64 queued coordinates, one per lane.
 // kBufs buffers (the parameters, then the optimizer states) share the mask and the permutation;
 // buffer b uses the slab at slab + b * N * 64.
@@ -88,30 +125,11 @@ __device__ __forceinline__ void permute_batch(const ShuffleArgs &a, uint32_t ste
         for (int b = 0; b < kBufs; ++b)
             gather_row_to_lds(col[b] + static_cast<uint64_t>(n) * P, slab + b * slab_words + n * kWave);
     }
-    // While the gathers are in flight, draw the permutation words and reduce them to the swap
-    // partners j_i of the descending Fisher-Yates walk (i = N-1 .. 1, j_i = (w * (i+1)) >> 32,
-    // four per Philox call, packed one byte each): they depend on the coordinate only.  The packs
-    // sit in a register ring that is rotated instead of indexed, so both loops stay rolled.
-    const uint32_t g_lo = static_cast<uint32_t>(g), g_hi = static_cast<uint32_t>(g >> 32);
+    // While the gathers are in flight, draw the swap partners: they depend on the coordinate only.
     const uint32_t nswaps = N - 1;
     const uint32_t ncalls = (nswaps + 3u) / 4u;             // <= kMaxCalls
-    uint32_t ring[kMaxCalls] = {0, 0, 0, 0, 0, 0, 0, 0};
-    for (uint32_t call = 0; call < kMaxCalls; ++call) {
-        // after kMaxCalls rotations the pack of call c sits in ring[c]
-        uint32_t pack = 0;
-        if (call < ncalls) {
-            const Words4 r = philox4x32_10(g_lo, g_hi, step, 1u + call, a.key_lo, a.key_hi);
-            const uint32_t w[4] = {r.w0, r.w1, r.w2, r.w3};
-#pragma unroll
-            for (uint32_t k = 0; k < 4; ++k) {
-                const uint32_t t = call * 4u + k;
-                if (t < nswaps) pack |= __umulhi(w[k], N - t) << (8u * k);   // i + 1 = N - t
-            }
-        }
-#pragma unroll
-        for (uint32_t q = 0; q + 1 < kMaxCalls; ++q) ring[q] = ring[q + 1];
-        ring[kMaxCalls - 1] = pack;
-    }
+    uint32_t ring[kMaxCalls];
+    draw_swap_partners(a, step, g, ring);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // The walk is applied to the values themselves: swapping slab rows i and j keeps
@@ -144,6 +162,35 @@ __device__ __forceinline__ void permute_batch(const ShuffleArgs &a, uint32_t ste
     if (moved & 1u) {
 #pragma unroll
         for (int b = 0; b < kBufs; ++b) col[b][0] = slab[b * slab_words + lane];
+    }
+}
+
+// The Bernoulli mask (Eq. 3) of the four coordinates 4*quad .. 4*quad+3: one Philox call, the four
+// words compared with the thresholds of the segments the coordinates lie in.  `uniform`: the whole
+// tile lies in segment seg0.  Otherwise `walk` is the lane's cursor into the segment table; the
+// coordinates of a lane only grow from call to call, so the cursor only moves forward.
+__device__ __forceinline__ void select_quad(const ShuffleArgs &a, uint32_t step, uint64_t quad, uint64_t tile_end,
+                                            bool uniform, const DevSegment &seg0, uint32_t &walk, bool (&sel)[4])
+{
+    const uint64_t g0 = quad << 2;
+    const Words4 r = philox4x32_10(static_cast<uint32_t>(quad), static_cast<uint32_t>(quad >> 32),
+                                   step, 0u, a.key_lo, a.key_hi);
+    const uint32_t w[4] = {r.w0, r.w1, r.w2, r.w3};
+    if (uniform) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) sel[k] = (w[k] <= static_cast<uint32_t>(seg0.param)) && (g0 + k < tile_end);
+    } else {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint64_t g = g0 + k;
+            while (walk < a.nsegs && a.segs[walk].end <= g) ++walk;
+            bool s = false;
+            if (walk < a.nsegs && g < tile_end) {
+                const DevSegment sg = a.segs[walk];
+                s = (sg.begin <= g) && (w[k] <= static_cast<uint32_t>(sg.param));
+            }
+            sel[k] = s;
+        }
     }
 }
 
@@ -180,27 +227,8 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
     for (uint32_t it = 0; it < iters; ++it) {
         const uint64_t quad = (tile_begin >> 2) + static_cast<uint64_t>(it) * kWave + lane;
         const uint64_t g0 = quad << 2;
-        const Words4 r = philox4x32_10(static_cast<uint32_t>(quad), static_cast<uint32_t>(quad >> 32),
-                                       step, 0u, a.key_lo, a.key_hi);
-        const uint32_t w[4] = {r.w0, r.w1, r.w2, r.w3};
         bool sel[4];
-        if (uniform) {
-#pragma unroll
-            for (int k = 0; k < 4; ++k) sel[k] = (w[k] <= static_cast<uint32_t>(seg0.param)) && (g0 + k < tile_end);
-        } else {
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const uint64_t g = g0 + k;
-                // coordinates of a lane only grow, so the cursor only moves forward
-                while (walk < a.nsegs && a.segs[walk].end <= g) ++walk;
-                bool s = false;
-                if (walk < a.nsegs && g < tile_end) {
-                    const DevSegment sg = a.segs[walk];
-                    s = (sg.begin <= g) && (w[k] <= static_cast<uint32_t>(sg.param));
-                }
-                sel[k] = s;
-            }
-        }
+        select_quad(a, step, quad, tile_end, uniform, seg0, walk, sel);
         if (__ballot(sel[0] | sel[1] | sel[2] | sel[3]) == 0) continue;
 
         // append in ascending coordinate order (lane-major, then k), so that neighbours in the
@@ -230,6 +258,122 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
     // memory side; spread them over kCountSlots cache lines and let a tiny kernel fold them.
     if (a.count_slots != nullptr && selected != 0 && lane == 0)
         atomicAdd(a.count_slots + (tile % kCountSlots) * kCountSlotStride, static_cast<unsigned long long>(selected));
+}
+
+// ---------------------------------------------------------------------------------------------
+// Dense variant of the same stream for high probabilities.  Once most 64-byte half lines of a row
+// hold a selected coordinate, scattered 4-byte accesses cost more than streaming the rows through
+// LDS: one wavefront (one workgroup) owns one strip of 256 coordinates, loads it from all N rows
+// of every buffer with coalesced global->LDS loads, permutes the selected columns in LDS (the same
+// mask, the same swap partners, hence the same bits as shuffle_kernel) and writes the rows back
+// with 16-byte stores.  Unselected coordinates of the strip are rewritten with their own values.
+constexpr uint32_t kStrip = 256;
+typedef uint32_t u4u __attribute__((ext_vector_type(4), aligned(4)));   // rows are only 4-byte aligned
+
+template <int kBufs>
+__global__ __launch_bounds__(kWave) void shuffle_dense_kernel(const ShuffleArgs a)
+{
+    extern __shared__ uint32_t lds[];
+    const uint32_t lane = lane_id();
+    const uint64_t tile = blockIdx.x;                 // the grid has exactly num_tiles workgroups
+    const uint32_t first = a.tile_first[tile];
+    if (first == kNoSegment) return;
+    const uint32_t step = step_of(a);
+    const uint32_t N = a.N;
+    const uint64_t P = a.P;
+    const uint64_t begin = tile * kStrip;
+    const uint64_t end = min(begin + kStrip, P);
+    const DevSegment seg0 = a.segs[first];
+    const bool uniform = seg0.begin <= begin && seg0.end >= end;
+
+    uint32_t walk = first;
+    bool sel[4];
+    select_quad(a, step, (begin >> 2) + lane, end, uniform, seg0, walk, sel);
+    const uint64_t b0 = __ballot(sel[0]), b1 = __ballot(sel[1]), b2 = __ballot(sel[2]), b3 = __ballot(sel[3]);
+    const uint32_t count = __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3);
+    if (count == 0) return;
+
+    // [selected offsets: 256 x u16][slab: kBufs x N rows x 256 coordinates]
+    uint16_t *picked = reinterpret_cast<uint16_t *>(lds);
+    uint32_t *slab = lds + kStrip / 2;
+    const uint32_t width = static_cast<uint32_t>(end - begin);      // 1 .. 256
+    // Non-temporal loads and stores together pay off on large populations (measured, both or neither:
+    // N = 20, P = 87 M: 3.15 -> 2.92 ms; N = 10, P = 26 M, two buffers: 0.86 -> 0.89 ms; one of
+    // the two alone is slower everywhere).
+    const bool nt = a.dense_nontemporal != 0;
+
+    // rows -> LDS: four loads of 64 consecutive words per row, lane l of load q brings coordinate 64 q + l
+    for (uint32_t n = 0; n < N; ++n) {
+#pragma unroll
+        for (int b = 0; b < kBufs; ++b) {
+            const uint32_t *row = a.bufs[b] + static_cast<uint64_t>(n) * P + begin;
+            uint32_t *dst = slab + (b * N + n) * kStrip;
+#pragma unroll
+            for (uint32_t q = 0; q < kStrip / kWave; ++q)
+                if (q * kWave + lane < width) {
+                    if (nt) stream_row_to_lds(row + q * kWave + lane, dst + q * kWave);
+                    else gather_row_to_lds(row + q * kWave + lane, dst + q * kWave);
+                }
+        }
+    }
+    // meanwhile: the selected offsets, ascending
+    uint32_t pos = lanes_below(b0) + lanes_below(b1) + lanes_below(b2) + lanes_below(b3);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        if (sel[k]) picked[pos++] = static_cast<uint16_t>(4u * lane + k);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    wave_lds_sync();
+
+    const uint32_t nswaps = N - 1;
+    const uint32_t ncalls = (nswaps + 3u) / 4u;
+    for (uint32_t done = 0; done < count; done += kWave) {
+        if (done + lane < count) {
+            const uint32_t c = picked[done + lane];
+            uint32_t ring[kMaxCalls];
+            draw_swap_partners(a, step, begin + c, ring);
+            uint32_t i = nswaps;
+            for (uint32_t call = 0; call < ncalls; ++call) {
+                const uint32_t pack = ring[0];
+#pragma unroll
+                for (uint32_t q = 0; q + 1 < kMaxCalls; ++q) ring[q] = ring[q + 1];
+#pragma unroll
+                for (uint32_t k = 0; k < 4; ++k) {
+                    if (i == 0) break;
+                    const uint32_t j = (pack >> (8u * k)) & 0xFFu;
+#pragma unroll
+                    for (int b = 0; b < kBufs; ++b) {
+                        uint32_t *colm = slab + b * N * kStrip + c;
+                        const uint32_t vi = colm[i * kStrip];
+                        const uint32_t vj = colm[j * kStrip];
+                        colm[i * kStrip] = vj;
+                        colm[j * kStrip] = vi;
+                    }
+                    --i;
+                }
+            }
+        }
+    }
+    wave_lds_sync();
+
+    // LDS -> rows: 16 bytes per lane (word by word in a ragged last strip)
+    const uint32_t c0 = 4u * lane;
+    for (uint32_t n = 0; n < N; ++n) {
+#pragma unroll
+        for (int b = 0; b < kBufs; ++b) {
+            uint32_t *row = a.bufs[b] + static_cast<uint64_t>(n) * P + begin;
+            const uint32_t *src = slab + (b * N + n) * kStrip + c0;
+            if (c0 + 4u <= width) {
+                const u4u v = {src[0], src[1], src[2], src[3]};
+                if (nt) __builtin_nontemporal_store(v, reinterpret_cast<u4u *>(row + c0));
+                else *reinterpret_cast<u4u *>(row + c0) = v;
+            } else {
+                for (uint32_t k = 0; c0 + k < width; ++k) row[c0 + k] = src[k];
+            }
+        }
+    }
+    if (a.count_slots != nullptr && lane == 0)
+        atomicAdd(a.count_slots + (tile % kCountSlots) * kCountSlotStride, static_cast<unsigned long long>(count));
 }
 
 // Runs after the shuffle kernel on the same stream.  Adds the per-slot partial counts to the caller's
@@ -393,6 +537,32 @@ hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream)
     case 2: hipLaunchKernelGGL(shuffle_kernel<2>, grid, block, lds_bytes, stream, a); break;
     case 3: hipLaunchKernelGGL(shuffle_kernel<3>, grid, block, lds_bytes, stream, a); break;
     default: hipLaunchKernelGGL(shuffle_kernel<4>, grid, block, lds_bytes, stream, a); break;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || (a.count_slots == nullptr && a.step_advance == nullptr)) return e;
+    hipLaunchKernelGGL(fold_count_kernel, dim3(1), dim3(kCountSlots), 0, stream, a.count_slots, a.selected_count,
+                       a.step_advance);
+    return hipGetLastError();
+}
+
+size_t shuffle_dense_lds_bytes(uint32_t N, uint32_t nbufs)
+{
+    return (kStrip / 2 + static_cast<size_t>(N) * nbufs * kStrip) * sizeof(uint32_t);
+}
+
+hipError_t launch_shuffle_dense(const ShuffleArgs &a, hipStream_t stream)
+{
+    if (a.num_tiles == 0 || a.nsegs == 0) return a.step_advance ? launch_step_advance(a.step_advance, stream) : hipSuccess;
+    if (a.nbufs == 0 || a.nbufs > kMaxBufs || a.tile_coords != kStrip) return hipErrorInvalidValue;
+    const size_t lds_bytes = shuffle_dense_lds_bytes(a.N, a.nbufs);
+    // the direct-to-LDS loads address LDS through a 16-bit offset
+    if (lds_bytes > 65536 || a.num_tiles > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
+    const dim3 grid(static_cast<uint32_t>(a.num_tiles)), block(kWave);
+    switch (a.nbufs) {
+    case 1: hipLaunchKernelGGL(shuffle_dense_kernel<1>, grid, block, lds_bytes, stream, a); break;
+    case 2: hipLaunchKernelGGL(shuffle_dense_kernel<2>, grid, block, lds_bytes, stream, a); break;
+    case 3: hipLaunchKernelGGL(shuffle_dense_kernel<3>, grid, block, lds_bytes, stream, a); break;
+    default: hipLaunchKernelGGL(shuffle_dense_kernel<4>, grid, block, lds_bytes, stream, a); break;
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || (a.count_slots == nullptr && a.step_advance == nullptr)) return e;

@@ -341,3 +341,37 @@ def test_randomised_shapes_segments_buffers(wash, case):
     ref = pop.copy()
     oracle.ema(ref, alpha)
     assert np.array_equal(_bits(d.cpu().numpy()), _bits(ref))
+
+
+@pytest.mark.parametrize("dense", [1, 2])
+@pytest.mark.parametrize("N,P,nbuf", [(2, 3, 1), (2, 255, 2), (3, 256, 3), (4, 257, 4), (5, 4097, 1), (10, 70_001, 2),
+                                      (20, 33_333, 3), (31, 5000, 2), (32, 20_011, 1), (8, 1_000_003, 2),
+                                      (15, 123_457, 4)])
+@pytest.mark.parametrize("p", [0.002, 0.07, 0.5, 1.0])
+def test_dense_and_sparse_paths_give_the_oracle_bits(wash, N, P, nbuf, p, dense):
+    # the dense path (whole strips of all rows through LDS) and the sparse path (gathers of single
+    # values) implement the same stream; option 2 forces the dense one wherever it fits, 1 forbids it
+    print(f"case N={N} P={P} nbuf={nbuf} p={p} dense={dense}", flush=True)
+    if P >= 64:
+        a, b = P // 3, P // 2
+        segs = [(0, a, p), (a + 5, b - a - 5, 1.0 if p < 1.0 else 0.3), (b, P - b - 1, p)]
+    else:
+        segs = [(0, P, p)]
+    bufs = [distinct_population(N, P, base=0x3F000000 + k * 0x01000000) for k in range(nbuf)]
+    refs, ref_cnt = [], 0
+    for b_ in bufs:
+        r = b_.copy()
+        ref_cnt = oracle.shuffle(r, None, segs, 31, 6)
+        refs.append(r)
+    dev = [torch.from_numpy(b_).cuda() for b_ in bufs]
+    cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+    wash.wash_set_option(wash.OPT_TILE_COORDS, 0)
+    wash.wash_set_option(wash.OPT_DENSE, dense)
+    try:
+        wash.wash_shuffle_states(dev, segs, 31, 6, selected_count=cnt)
+        torch.cuda.synchronize()
+    finally:
+        wash.wash_set_option(wash.OPT_DENSE, 0)
+    assert int(cnt.item()) == ref_cnt
+    for d, r in zip(dev, refs):
+        assert np.array_equal(_bits(d.cpu().numpy()), _bits(r))
