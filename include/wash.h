@@ -84,9 +84,9 @@ typedef struct wash_segment {
  *   P               coordinates per model, >= 1
  *   segs            HOST array of nsegs segments, sorted by offset and not
  *                   overlapping; read before the call returns.  Coordinates in
- *                   no segment are never shuffled.  (When every segment has
+ *                   no segment are never shuffled.  (Inside segments with
  *                   p >= 0.08 the rows are streamed through on-chip memory in
- *                   strips of 256 coordinates, and the call may then rewrite
+ *                   aligned strips of 256 coordinates, and the call may rewrite
  *                   any element of such a strip with the value it already has;
  *                   see WASH_OPT_DENSE.)
  *   nsegs           number of segments (0 allowed: nothing happens)
@@ -274,8 +274,8 @@ const char *wash_last_error_detail(void);
  *                         or 0 = choose by N and P (8 for N >= 10 and P >= 2^26, else 1 or 4)
  *   WASH_OPT_DENSE        wash_shuffle has a second code path that streams whole rows through
  *                         on-chip memory instead of gathering single values (same results);
- *                         0 = use it when every segment's probability is high enough for it
- *                         to be faster, 1 = never, 2 = whenever N * buffers <= 63
+ *                         0 = use it inside segments whose probability is high enough for it
+ *                         to be faster (p >= 0.08), 1 = never, 2 = wherever N * buffers <= 63
  */
 #define WASH_OPT_TILE_COORDS 1
 #define WASH_OPT_AVERAGE_CHUNKS 4

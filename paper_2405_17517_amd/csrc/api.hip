@@ -236,8 +236,6 @@ static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t
         return fail(WASH_ENOMEM, "segment list");
     }
     uint64_t prev_end = 0;
-    double expected_selected = 0.0;     // of the default stream: sum of p * length (a launch-shape input only)
-    uint64_t min_threshold = 1ull << 32; // smallest threshold of an active segment of the default stream
     for (uint32_t s = 0; s < nsegs; ++s) {
         const wash_segment &sg = segs[s];
         if (!(sg.p >= 0.0 && sg.p <= 1.0))
@@ -263,8 +261,6 @@ static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t
         }
         const uint64_t T = threshold_of(sg.p);
         if (T == 0) continue;                       // never selected: not scanned at all
-        expected_selected += static_cast<double>(T) / 4294967296.0 * static_cast<double>(sg.length);
-        if (T < min_threshold) min_threshold = T;
         wash::DevSegment d{sg.offset, sg.offset + sg.length, T - 1u};
         // neighbours with the same threshold behave as one segment
         if (!active.empty() && active.back().end == d.begin && active.back().param == d.param)
@@ -301,48 +297,46 @@ static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t
     if (e != hipSuccess) return fail_hip("hipGetDevice", e);
 
     std::lock_guard<std::mutex> lock(g_mutex);
-    // Dense path of the default stream: streaming a 256-coordinate strip of all rows through LDS costs the same
-    // whatever p is, the sparse path's scattered accesses grow with p until every half line is touched.
-    // Measured crossover at p = 0.08 (N = 20, P = 87 M: dense 2.92 ms; sparse 2.38 ms at p = 0.05, 2.79 at 0.07,
-    // 3.20 at 0.1, 3.57 from 0.25 on.  N = 10, P = 26 M, two buffers: dense 0.82-0.86 ms; sparse 0.68 at 0.05,
-    // 0.91 at 0.1, 1.03 at 1).  It is used when every active segment is at least that dense.
-    const bool dense_fits = N >= 2 && wash::shuffle_dense_lds_bytes(N, nbufs) <= 65536;
-    const bool dense = !gap && dense_fits && g_tile_coords_option == 0 &&
-                       (g_dense_option == 2 || (g_dense_option == 0 && min_threshold >= threshold_of(0.08)));
-    const uint32_t tile_coords =
-        gap ? wash::kGapPiece
-            : dense ? 256u : choose_tile_coords(P, expected_selected / static_cast<double>(P) * N * nbufs);
-    Table *table = nullptr;
-    if (int rc = get_table(device, P, tile_coords, gap, std::move(active), &table)) return rc;
-    // A launch recorded into a graph keeps using this table at every replay: never evict it.
+    const hipStream_t hstream = static_cast<hipStream_t>(stream);
+    bool capturing = false;
     if (stream != nullptr) {
         hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
-        if (hipStreamIsCapturing(static_cast<hipStream_t>(stream), &capture) != hipSuccess)
+        if (hipStreamIsCapturing(hstream, &capture) != hipSuccess)
             (void)hipGetLastError();
-        else if (capture == hipStreamCaptureStatusActive)
-            table->pinned = true;
+        else
+            capturing = capture == hipStreamCaptureStatusActive;
     }
+    // Finds or builds the device table of `list` and fills the kernel arguments that go with it.
+    auto prepare = [&](std::vector<wash::DevSegment> &&list, uint32_t tile_coords, wash::ShuffleArgs *a) -> int {
+        Table *table = nullptr;
+        if (int rc = get_table(device, P, tile_coords, gap, std::move(list), &table)) return rc;
+        // a launch recorded into a graph keeps using this table at every replay: never evict it
+        if (capturing) table->pinned = true;
+        *a = wash::ShuffleArgs{};
+        for (uint32_t b = 0; b < nbufs; ++b) a->bufs[b] = reinterpret_cast<uint32_t *>(bufs[b]);
+        a->nbufs = nbufs;
+        a->N = N;
+        a->P = P;
+        unsigned char *base = static_cast<unsigned char *>(table->dev);
+        a->segs = reinterpret_cast<const wash::DevSegment *>(base + wash::kCountSlotBytes);
+        a->nsegs = static_cast<uint32_t>(table->key.segs.size());
+        a->tile_first = reinterpret_cast<const uint32_t *>(base + wash::kCountSlotBytes +
+                                                           table->key.segs.size() * sizeof(wash::DevSegment));
+        a->num_tiles = table->num_tiles;
+        a->tile_coords = tile_coords;
+        a->key_lo = static_cast<uint32_t>(seed);
+        a->key_hi = static_cast<uint32_t>(seed >> 32);
+        a->step = static_cast<uint32_t>(step);
+        a->step_ptr = reinterpret_cast<const unsigned long long *>(step_dev);
+        a->step_advance = (step_dev != nullptr && advance) ? reinterpret_cast<unsigned long long *>(step_dev) : nullptr;
+        a->selected_count = reinterpret_cast<unsigned long long *>(selected_count);
+        a->count_slots = selected_count ? reinterpret_cast<unsigned long long *>(base) : nullptr;
+        return WASH_OK;
+    };
 
-    wash::ShuffleArgs a{};
-    for (uint32_t b = 0; b < nbufs; ++b) a.bufs[b] = reinterpret_cast<uint32_t *>(bufs[b]);
-    a.nbufs = nbufs;
-    a.N = N;
-    a.P = P;
-    unsigned char *base = static_cast<unsigned char *>(table->dev);
-    a.segs = reinterpret_cast<const wash::DevSegment *>(base + wash::kCountSlotBytes);
-    a.nsegs = static_cast<uint32_t>(table->key.segs.size());
-    a.tile_first = reinterpret_cast<const uint32_t *>(base + wash::kCountSlotBytes +
-                                                      table->key.segs.size() * sizeof(wash::DevSegment));
-    a.num_tiles = table->num_tiles;
-    a.tile_coords = tile_coords;
-    a.key_lo = static_cast<uint32_t>(seed);
-    a.key_hi = static_cast<uint32_t>(seed >> 32);
-    a.step = static_cast<uint32_t>(step);
-    a.step_ptr = reinterpret_cast<const unsigned long long *>(step_dev);
-    a.step_advance = (step_dev != nullptr && advance) ? reinterpret_cast<unsigned long long *>(step_dev) : nullptr;
-    a.selected_count = reinterpret_cast<unsigned long long *>(selected_count);
-    a.count_slots = selected_count ? reinterpret_cast<unsigned long long *>(base) : nullptr;
     if (gap) {
+        wash::ShuffleArgs a;
+        if (int rc = prepare(std::move(active), wash::kGapPiece, &a)) return rc;
         // Blocks walked by one wavefront.  The kernel is bound by the scattered read-modify-write rate as soon
         // as a few coordinates per block are selected, and that rate grows with the number of batches in
         // flight, i.e. with the number of wavefronts: aim at about 16 finds per wavefront (measured best from
@@ -352,13 +346,58 @@ static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t
         while (bpw > 1 && a.num_tiles / bpw < 2048) bpw >>= 1;
         if (g_gap_blocks_option != 0) bpw = static_cast<uint32_t>(g_gap_blocks_option);
         a.blocks_per_wave = bpw;
-        e = wash::launch_shuffle_gap(a, static_cast<hipStream_t>(stream));
-    } else if (dense) {
-        a.dense_nontemporal = pop_bytes * nbufs >= (4ull << 30) ? 1u : 0u;
-        e = wash::launch_shuffle_dense(a, static_cast<hipStream_t>(stream));
-    } else {
-        e = wash::launch_shuffle(a, static_cast<hipStream_t>(stream));
+        e = wash::launch_shuffle_gap(a, hstream);
+        if (e != hipSuccess) return fail_hip("shuffle launch", e);
+        return WASH_OK;
     }
+
+    // Default stream.  Streaming a 256-coordinate strip of all rows through LDS (the dense kernel) costs the
+    // same whatever p is; the sparse kernel's scattered accesses grow with p until every half line is touched.
+    // Measured crossover at p = 0.08 (N = 20, P = 87 M: dense 2.92 ms; sparse 2.38 ms at p = 0.05, 2.79 at 0.07,
+    // 3.20 at 0.1, 3.57 from 0.25 on.  N = 10, P = 26 M, two buffers: dense 0.82-0.86 ms; sparse 0.68 at 0.05,
+    // 0.91 at 0.1, 1.03 at 1).  The whole strips inside segments at least that dense go to the dense kernel, the
+    // rest of the list (sparser segments, and the ragged ends of dense ones) to the sparse kernel; the stream is
+    // addressed by the coordinate, so the split changes no bit.
+    const bool dense_fits = N >= 2 && wash::shuffle_dense_lds_bytes(N, nbufs) <= 65536;
+    const bool dense_allowed = dense_fits && g_tile_coords_option == 0 && g_dense_option != 1;
+    const uint64_t dense_threshold = g_dense_option == 2 ? 1 : threshold_of(0.08);
+    std::vector<wash::DevSegment> dense_list, sparse_list;
+    double expected_sparse = 0.0;
+    try {
+        for (const wash::DevSegment &d : active) {
+            uint64_t b = d.begin, t = d.end;
+            if (dense_allowed && d.param + 1 >= dense_threshold) {
+                b = (d.begin + 255u) / 256u * 256u;
+                t = d.end == P ? P : d.end / 256u * 256u;
+            }
+            if (!dense_allowed || d.param + 1 < dense_threshold || b >= t) {
+                sparse_list.push_back(d);
+                continue;
+            }
+            if (d.begin < b) sparse_list.push_back(wash::DevSegment{d.begin, b, d.param});
+            dense_list.push_back(wash::DevSegment{b, t, d.param});
+            if (t < d.end) sparse_list.push_back(wash::DevSegment{t, d.end, d.param});
+        }
+    } catch (const std::bad_alloc &) {
+        return fail(WASH_ENOMEM, "segment list");
+    }
+    for (const wash::DevSegment &d : sparse_list)
+        expected_sparse += static_cast<double>(d.param + 1) / 4294967296.0 * static_cast<double>(d.end - d.begin);
+    const bool have_dense = !dense_list.empty(), have_sparse = !sparse_list.empty();
+    wash::ShuffleArgs ad, as;
+    if (have_dense)
+        if (int rc = prepare(std::move(dense_list), 256u, &ad)) return rc;
+    if (have_sparse)
+        if (int rc = prepare(std::move(sparse_list),
+                             choose_tile_coords(P, expected_sparse / static_cast<double>(P) * N * nbufs), &as))
+            return rc;
+    if (have_dense) {
+        if (have_sparse) ad.count_slots = as.count_slots;     // one set of partial counters, folded once
+        ad.dense_nontemporal = pop_bytes * nbufs >= (4ull << 30) ? 1u : 0u;
+        e = wash::launch_shuffle_dense(ad, hstream, /*finish=*/!have_sparse);
+        if (e != hipSuccess) return fail_hip("shuffle launch", e);
+    }
+    if (have_sparse) e = wash::launch_shuffle(as, hstream, /*finish=*/true);
     if (e != hipSuccess) return fail_hip("shuffle launch", e);
     return WASH_OK;
 }

@@ -29,7 +29,7 @@ struct ShuffleArgs {
     uint32_t tile_coords;       // stream v1: coordinates per tile (one wavefront scans one tile), multiple of 256
                                 // gap stream: 1024 (a tile is one restart block; a wavefront walks `blocks_per_wave` of them)
     uint32_t blocks_per_wave;   // gap stream only: 1 .. 64
-    uint32_t dense_nontemporal; // dense path only: stream the rows past the caches
+    uint32_t dense_nontemporal; // dense path only, read by the launcher: stream the rows past the caches
     uint32_t key_lo, key_hi;    // seed
     uint32_t step;              // used when step_ptr is nullptr
     const unsigned long long *step_ptr; // device step counter read by the kernel (its low 32 bits), or nullptr
@@ -43,11 +43,13 @@ constexpr uint32_t kCountSlots = 256;
 constexpr uint32_t kCountSlotStride = 16;   // in 8-byte words
 constexpr size_t kCountSlotBytes = static_cast<size_t>(kCountSlots) * kCountSlotStride * 8;
 
-hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream);
+// finish: fold the selected count and advance the device step after the kernel (false for all but the last
+// kernel of a call that launches several)
+hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream, bool finish = true);
 hipError_t launch_shuffle_gap(const ShuffleArgs &a, hipStream_t stream);
 // dense variant of launch_shuffle (same results): tile_coords must be 256; needs shuffle_dense_lds_bytes <= 64 KiB
 size_t shuffle_dense_lds_bytes(uint32_t N, uint32_t nbufs);
-hipError_t launch_shuffle_dense(const ShuffleArgs &a, hipStream_t stream);
+hipError_t launch_shuffle_dense(const ShuffleArgs &a, hipStream_t stream, bool finish = true);
 hipError_t launch_step_advance(unsigned long long *step_advance, hipStream_t stream);   // *step_advance += 1
 hipError_t launch_average(const float *params, float *out, uint32_t N, uint64_t P, int chunks_per_block,
                           hipStream_t stream);

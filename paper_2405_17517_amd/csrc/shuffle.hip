@@ -85,6 +85,7 @@ __device__ __forceinline__ void draw_swap_partners(const ShuffleArgs &a, uint32_
     const uint32_t ncalls = (nswaps + 3u) / 4u;             // <= kMaxCalls
 #pragma unroll
     for (uint32_t q = 0; q < kMaxCalls; ++q) ring[q] = 0;
+#pragma unroll 1
     for (uint32_t call = 0; call < kMaxCalls; ++call) {
         uint32_t pack = 0;
         if (call < ncalls) {
@@ -270,7 +271,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
 constexpr uint32_t kStrip = 256;
 typedef uint32_t u4u __attribute__((ext_vector_type(4), aligned(4)));   // rows are only 4-byte aligned
 
-template <int kBufs>
+template <int kBufs, bool kStream>
 __global__ __launch_bounds__(kWave) void shuffle_dense_kernel(const ShuffleArgs a)
 {
     extern __shared__ uint32_t lds[];
@@ -297,10 +298,11 @@ __global__ __launch_bounds__(kWave) void shuffle_dense_kernel(const ShuffleArgs 
     uint16_t *picked = reinterpret_cast<uint16_t *>(lds);
     uint32_t *slab = lds + kStrip / 2;
     const uint32_t width = static_cast<uint32_t>(end - begin);      // 1 .. 256
-    // Non-temporal loads and stores together pay off on large populations (measured, both or neither:
-    // N = 20, P = 87 M: 3.15 -> 2.92 ms; N = 10, P = 26 M, two buffers: 0.86 -> 0.89 ms; one of
-    // the two alone is slower everywhere).
-    const bool nt = a.dense_nontemporal != 0;
+    // kStream: non-temporal loads and stores.  Together they pay off on large populations (measured, both
+    // or neither: N = 20, P = 87 M: 3.15 -> 2.92 ms; N = 10, P = 26 M, two buffers: 0.86 -> 0.89 ms; one of
+    // the two alone is slower everywhere, 3.70 ms with the loads alone).  A template parameter and not a
+    // run-time flag: the two stores of a run-time branch are merged into one plain store.
+    constexpr bool nt = kStream;
 
     // rows -> LDS: four loads of 64 consecutive words per row, lane l of load q brings coordinate 64 q + l
     for (uint32_t n = 0; n < N; ++n) {
@@ -519,9 +521,18 @@ hipError_t launch_step_advance(unsigned long long *step_advance, hipStream_t str
     return hipGetLastError();
 }
 
-hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream)
+// the kernel that follows the last shuffle kernel of a call
+static hipError_t finish_call(const ShuffleArgs &a, hipStream_t stream)
 {
-    if (a.num_tiles == 0 || a.nsegs == 0) return a.step_advance ? launch_step_advance(a.step_advance, stream) : hipSuccess;
+    if (a.count_slots == nullptr && a.step_advance == nullptr) return hipSuccess;
+    hipLaunchKernelGGL(fold_count_kernel, dim3(1), dim3(kCountSlots), 0, stream, a.count_slots, a.selected_count,
+                       a.step_advance);
+    return hipGetLastError();
+}
+
+hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream, bool finish)
+{
+    if (a.num_tiles == 0 || a.nsegs == 0) return finish ? finish_call(a, stream) : hipSuccess;
     // the direct-to-LDS loads address LDS through a 16-bit offset: keep a block's partition below 64 KiB
     if (a.nbufs == 0 || a.nbufs > kMaxBufs) return hipErrorInvalidValue;
     const size_t per_wave = (kQueueCap / 2 + static_cast<size_t>(a.N) * kWave * a.nbufs) * sizeof(uint32_t);
@@ -538,11 +549,9 @@ hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream)
     case 3: hipLaunchKernelGGL(shuffle_kernel<3>, grid, block, lds_bytes, stream, a); break;
     default: hipLaunchKernelGGL(shuffle_kernel<4>, grid, block, lds_bytes, stream, a); break;
     }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || (a.count_slots == nullptr && a.step_advance == nullptr)) return e;
-    hipLaunchKernelGGL(fold_count_kernel, dim3(1), dim3(kCountSlots), 0, stream, a.count_slots, a.selected_count,
-                       a.step_advance);
-    return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess || !finish) return e;
+    return finish_call(a, stream);
 }
 
 size_t shuffle_dense_lds_bytes(uint32_t N, uint32_t nbufs)
@@ -550,30 +559,38 @@ size_t shuffle_dense_lds_bytes(uint32_t N, uint32_t nbufs)
     return (kStrip / 2 + static_cast<size_t>(N) * nbufs * kStrip) * sizeof(uint32_t);
 }
 
-hipError_t launch_shuffle_dense(const ShuffleArgs &a, hipStream_t stream)
+hipError_t launch_shuffle_dense(const ShuffleArgs &a, hipStream_t stream, bool finish)
 {
-    if (a.num_tiles == 0 || a.nsegs == 0) return a.step_advance ? launch_step_advance(a.step_advance, stream) : hipSuccess;
+    if (a.num_tiles == 0 || a.nsegs == 0) return finish ? finish_call(a, stream) : hipSuccess;
     if (a.nbufs == 0 || a.nbufs > kMaxBufs || a.tile_coords != kStrip) return hipErrorInvalidValue;
     const size_t lds_bytes = shuffle_dense_lds_bytes(a.N, a.nbufs);
     // the direct-to-LDS loads address LDS through a 16-bit offset
     if (lds_bytes > 65536 || a.num_tiles > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
     const dim3 grid(static_cast<uint32_t>(a.num_tiles)), block(kWave);
-    switch (a.nbufs) {
-    case 1: hipLaunchKernelGGL(shuffle_dense_kernel<1>, grid, block, lds_bytes, stream, a); break;
-    case 2: hipLaunchKernelGGL(shuffle_dense_kernel<2>, grid, block, lds_bytes, stream, a); break;
-    case 3: hipLaunchKernelGGL(shuffle_dense_kernel<3>, grid, block, lds_bytes, stream, a); break;
-    default: hipLaunchKernelGGL(shuffle_dense_kernel<4>, grid, block, lds_bytes, stream, a); break;
+    if (a.dense_nontemporal) {
+        switch (a.nbufs) {
+        case 1: hipLaunchKernelGGL((shuffle_dense_kernel<1, true>), grid, block, lds_bytes, stream, a); break;
+        case 2: hipLaunchKernelGGL((shuffle_dense_kernel<2, true>), grid, block, lds_bytes, stream, a); break;
+        case 3: hipLaunchKernelGGL((shuffle_dense_kernel<3, true>), grid, block, lds_bytes, stream, a); break;
+        default: hipLaunchKernelGGL((shuffle_dense_kernel<4, true>), grid, block, lds_bytes, stream, a); break;
+        }
+    } else {
+        switch (a.nbufs) {
+        case 1: hipLaunchKernelGGL((shuffle_dense_kernel<1, false>), grid, block, lds_bytes, stream, a); break;
+        case 2: hipLaunchKernelGGL((shuffle_dense_kernel<2, false>), grid, block, lds_bytes, stream, a); break;
+        case 3: hipLaunchKernelGGL((shuffle_dense_kernel<3, false>), grid, block, lds_bytes, stream, a); break;
+        default: hipLaunchKernelGGL((shuffle_dense_kernel<4, false>), grid, block, lds_bytes, stream, a); break;
+        }
     }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || (a.count_slots == nullptr && a.step_advance == nullptr)) return e;
-    hipLaunchKernelGGL(fold_count_kernel, dim3(1), dim3(kCountSlots), 0, stream, a.count_slots, a.selected_count,
-                       a.step_advance);
-    return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess || !finish) return e;
+    return finish_call(a, stream);
 }
 
 hipError_t launch_shuffle_gap(const ShuffleArgs &a, hipStream_t stream)
 {
-    if (a.num_tiles == 0 || a.nsegs == 0) return a.step_advance ? launch_step_advance(a.step_advance, stream) : hipSuccess;
+    const bool finish = true;
+    if (a.num_tiles == 0 || a.nsegs == 0) return finish_call(a, stream);
     if (a.blocks_per_wave == 0 || a.blocks_per_wave > kWave || a.tile_coords != kGapPiece)
         return hipErrorInvalidValue;
     if ((a.blocks_per_wave & (a.blocks_per_wave - 1)) != 0) return hipErrorInvalidValue;   // lists share 512 slots evenly
@@ -592,11 +609,9 @@ hipError_t launch_shuffle_gap(const ShuffleArgs &a, hipStream_t stream)
     case 3: hipLaunchKernelGGL(shuffle_gap_kernel<3>, grid, block, per_wave * waves, stream, a); break;
     default: hipLaunchKernelGGL(shuffle_gap_kernel<4>, grid, block, per_wave * waves, stream, a); break;
     }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || (a.count_slots == nullptr && a.step_advance == nullptr)) return e;
-    hipLaunchKernelGGL(fold_count_kernel, dim3(1), dim3(kCountSlots), 0, stream, a.count_slots, a.selected_count,
-                       a.step_advance);
-    return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess || !finish) return e;
+    return finish_call(a, stream);
 }
 
 }  // namespace wash

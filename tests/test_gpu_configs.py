@@ -242,3 +242,34 @@ def test_coordinates_beyond_two_to_the_32(wash, stream):
         abs_mean = np.abs(ref).mean(axis=0)
         oracle.ema(ref, 0.75)
         assert _close(pop[:, g0:g0 + w].contiguous().cpu().numpy(), ref, abs_mean[None, :]), f"EMA window {g0}"
+
+
+@pytest.mark.parametrize("base_p", [0.5, 1.0])
+def test_layerwise_schedule_with_a_large_base_probability(wash, base_p):
+    """Eq. 6 on the ResNet-18 tensor list with the base probabilities of the paper's ablation: the
+    first tensors are dense enough for the streaming path, the last ones are not, so one call runs
+    both kernels on their parts of the list.  Two steps, momentum moved along, whole population
+    compared with the oracle."""
+    from workloads import layouts
+    cfg = get_config(2)
+    tensors = cfg.tensors()
+    probs = wash.wash_layer_probs(base_p, len(tensors), 0)
+    assert probs[0] == base_p and probs[-1] == 0.0 and min(probs[:-1]) > 0.0
+    segs_list = layouts.segments_of(tensors, probs)
+    segs = wash.SegmentList(segs_list)
+    pop, _ = device_population(tensors, cfg.N, cfg.init, cfg.data_seed, False)
+    mom = torch.randn(cfg.N, cfg.P, device="cuda", generator=torch.Generator(device="cuda").manual_seed(3)) * 1e-3
+    ref, refm = pop.cpu().numpy(), mom.cpu().numpy()
+    cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+    ref_cnt = 0
+    for step in range(2):
+        print(f"layer-wise schedule base {base_p} step {step}", flush=True)
+        wash.wash_shuffle(pop, mom, segs, 11, step, cnt)
+        ref_cnt += oracle.shuffle(ref, refm, segs_list, 11, step, threads=THREADS)
+    torch.cuda.synchronize()
+    assert int(cnt.item()) == ref_cnt
+    # Table 1's volume: half of base_p * d per step when every layer has the same size; here weighted by size
+    expect = 2 * sum(length * p for _, length, p in segs_list)
+    assert abs(ref_cnt - expect) < 6 * math.sqrt(expect)
+    assert np.array_equal(_bits(pop.cpu().numpy()), _bits(ref))
+    assert np.array_equal(_bits(mom.cpu().numpy()), _bits(refm))
