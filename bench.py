@@ -396,7 +396,8 @@ def main():
         "shuffle_elements_per_s": main_res["shuffle_elements_per_s"],
         # every moved value needs a scattered store: expected distinct 64-byte half lines written per second,
         # against the measured rate of scattered stores (the shuffle's practical ceiling once the population is
-        # large and p is high enough for the writes to outweigh the mask scan)
+        # large and p is high enough for the writes to outweigh the mask scan; from p = 0.08 the library streams
+        # whole rows instead of scattering, and this ratio no longer bounds anything)
         "shuffle_vs_scattered_stores": {
             "bound": "scattered-store", "achieved": main_res["shuffle_store_units_per_s"] / 1e9,
             "peak": scat["stores_Gelem_per_s"], "unit": "G half-lines/s",
