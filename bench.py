@@ -275,8 +275,18 @@ def cpu_baseline(cfg, budget_s=20.0):
         parts["wash_average"] += t3 - t2
         t_spent += t3 - t0
         passes += 1
+    # the oracle's shuffle also runs over all host cores (coordinates are independent and the stream is
+    # addressed by the coordinate, so the bits are the same); a few calls, reported beside the baseline
+    threads = max(1, min(16, os.cpu_count() or 1))
+    mt_calls, mt_spent = 0, 0.0
+    while mt_calls < 3 or (mt_spent < 2.0 and mt_calls < 50):
+        t0 = time.perf_counter()
+        oracle.shuffle(pop, mom, segs, cfg.seed, 1000 + mt_calls, threads=threads)
+        mt_spent += time.perf_counter() - t0
+        mt_calls += 1
     return {
         "value": cfg.P * passes / t_spent, "unit": "coords/s", "cores": 1, "kind": "oracle",
+        "shuffle_all_cores": {"threads": threads, "us_per_call": mt_spent / mt_calls * 1e6, "calls": mt_calls},
         "sample": f"{passes} whole passes (shuffle + EMA + average) over the full config-{cfg.index} population, "
                   f"{t_spent:.1f} s of CPU time",
         "ms_per_step": t_spent / passes * 1e3,
