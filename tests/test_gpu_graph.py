@@ -162,3 +162,40 @@ def test_table_of_a_captured_launch_survives_cache_eviction(wash):
         torch.cuda.synchronize()
         oracle.shuffle(ref, None, segs_list, 2, replay)
         assert np.array_equal(pop.cpu().numpy().view(np.uint32), ref.view(np.uint32)), replay
+
+
+def test_captured_call_that_uses_both_kernels(wash):
+    # a list with a dense segment (p = 0.6, streamed through LDS), a sparse one and ragged ends uses two
+    # segment tables and two kernels per call; both tables must survive later lists, the step advances once
+    N, P = 6, 90_011
+    rng = np.random.default_rng(21)
+    hosts = [(rng.standard_normal((N, P)) * 0.02).astype(np.float32) for _ in range(2)]
+    segs_list = [(7, 40_000, 0.6), (40_007, 30_000, 0.003), (75_000, P - 75_000, 1.0)]
+    segs = wash.SegmentList(segs_list)
+    bufs = [torch.from_numpy(h).cuda() for h in hosts]
+    step = torch.full((1,), 5, dtype=torch.int64, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+    wash.wash_shuffle_device_step(bufs, segs, 77, step, advance=False, selected_count=cnt)   # builds both tables
+    torch.cuda.synchronize()
+    for b, h in zip(bufs, hosts):
+        b.copy_(torch.from_numpy(h))
+    cnt.zero_()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        wash.wash_shuffle_device_step(bufs, segs, 77, step, advance=True, selected_count=cnt)
+    refs = [h.copy() for h in hosts]
+    ref_cnt = 0
+    for replay in range(3):
+        other = torch.from_numpy(hosts[0]).cuda()
+        for k in range(18):
+            wash.wash_shuffle(other, None, [(k + 3 + 50 * replay, 2000 + k, 0.2)], 0, 0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for r in refs:
+            c = oracle.shuffle(r, None, segs_list, 77, 5 + replay)
+        ref_cnt += c
+        assert int(step.item()) == 6 + replay
+        assert int(cnt.item()) == ref_cnt
+        for b, r in zip(bufs, refs):
+            assert np.array_equal(b.cpu().numpy().view(np.uint32), r.view(np.uint32)), replay
