@@ -1,8 +1,11 @@
-// wash_shuffle kernel for gfx950: the shuffling step of WASH (Sec. 3, Eq. 3;
-// Alg. 1, shuffling step), with the optimizer state moved along (WASH+Opt).
+// wash_shuffle kernels for gfx950: the shuffling step of WASH (Sec. 3, Eq. 3;
+// Alg. 1, shuffling step), with the optimizer state(s) moved along (WASH+Opt).
+// Three kernels: shuffle_kernel (default stream, sparse: gathers single values),
+// shuffle_dense_kernel (default stream, p >= 0.08: streams whole strips through
+// LDS; same bits) and shuffle_gap_kernel (gap-sampled mask stream).
 //
-// One wavefront owns one tile of consecutive coordinates and works alone (no
-// workgroup barrier anywhere):
+// shuffle_kernel: one wavefront owns one tile of consecutive coordinates and
+// works alone (no workgroup barrier anywhere):
 //   scan     each lane draws the mask words of 4 consecutive coordinates with
 //            one Philox call and compares them with the segment threshold;
 //            the Bernoulli mask is never written to memory.
