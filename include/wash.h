@@ -271,7 +271,7 @@ const char *wash_last_error_detail(void);
  *   WASH_OPT_GAP_BLOCKS   1024-coordinate blocks walked by one wavefront in wash_shuffle_gap;
  *                         a power of two in [1, 64], or 0 = choose by P and p
  *   WASH_OPT_AVERAGE_CHUNKS  1024-coordinate chunks owned by one block of wash_average: 1, 2, 4, 8,
- *                         or 0 = choose by N and P (8 for N >= 10 and P >= 2^26, else 1 or 4)
+ *                         or 0 = choose by N and P (8 when many long rows are read, else 1 or 4)
  *   WASH_OPT_DENSE        wash_shuffle has a second code path that streams whole rows through
  *                         on-chip memory instead of gathering single values (same results);
  *                         0 = use it inside segments whose probability is high enough for it

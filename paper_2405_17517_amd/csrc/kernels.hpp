@@ -70,11 +70,14 @@ hipError_t launch_sqdist(const float *params, uint32_t N, uint64_t P, uint64_t g
 hipError_t launch_scatter_probe(uint32_t *buf, uint64_t lines, int mode, uint32_t rounds, uint32_t blocks,
                                 uint32_t *sink, hipStream_t stream);
 // Chunks of 1024 coordinates owned by one block of the (weighted) average.  Long runs per row pay
-// off once many rows are read concurrently and enough blocks remain to fill the chip several times
-// over (measured, 8 TB/s = 100 %: N = 20, P = 87 M: 73 % -> 80 %; N = 8, P = 1.1 G: 76 % -> 68 %).
+// off once many rows are read concurrently and enough blocks remain to fill the chip (measured,
+// 8 TB/s = 100 %, 1 chunk -> 8 chunks: N = 20, P = 87 M: 73 % -> 81 %; N = 10, P = 60 M: 76 -> 83;
+// N = 32, P = 20 M: 77 -> 82; N = 16, P = 40 M: 76 -> 80 with 4; but N = 10, P = 26 M: 75 -> 71 and
+// N = 8, P = 1.1 G: 77 -> 68).
 inline int average_chunks_for(uint32_t N, uint64_t P)
 {
-    if (N >= 10 && P >= (1ull << 26)) return 8;
+    if (N >= 10 && P >= 40000000ull) return 8;
+    if (N >= 24 && P >= 16000000ull) return 8;
     if (N >= 16 && P >= (1ull << 25)) return 4;
     return 1;
 }
