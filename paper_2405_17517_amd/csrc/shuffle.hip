@@ -272,6 +272,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
 // mask, the same swap partners, hence the same bits as shuffle_kernel) and writes the rows back
 // with 16-byte stores.  Unselected coordinates of the strip are rewritten with their own values.
 constexpr uint32_t kStrip = 256;
+constexpr uint32_t kXcds = 8;
 typedef uint32_t u4u __attribute__((ext_vector_type(4), aligned(4)));   // rows are only 4-byte aligned
 
 template <int kBufs, bool kStream>
@@ -279,7 +280,12 @@ __global__ __launch_bounds__(kWave) void shuffle_dense_kernel(const ShuffleArgs 
 {
     extern __shared__ uint32_t lds[];
     const uint32_t lane = lane_id();
-    const uint64_t tile = blockIdx.x;                 // the grid has exactly num_tiles workgroups
+    // Workgroups are handed to the 8 XCDs round robin, and each XCD has its own L2.  Give every XCD one
+    // contiguous run of strips, so that the cache line two neighbouring strips share when rows are not
+    // 128-byte aligned is fetched into one L2 only.
+    const uint64_t per_xcd = (a.num_tiles + kXcds - 1) / kXcds;
+    const uint64_t tile = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    if (tile >= a.num_tiles) return;
     const uint32_t first = a.tile_first[tile];
     if (first == kNoSegment) return;
     const uint32_t step = step_of(a);
@@ -569,7 +575,9 @@ hipError_t launch_shuffle_dense(const ShuffleArgs &a, hipStream_t stream, bool f
     const size_t lds_bytes = shuffle_dense_lds_bytes(a.N, a.nbufs);
     // the direct-to-LDS loads address LDS through a 16-bit offset
     if (lds_bytes > 65536 || a.num_tiles > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
-    const dim3 grid(static_cast<uint32_t>(a.num_tiles)), block(kWave);
+    const uint64_t blocks64 = (a.num_tiles + kXcds - 1) / kXcds * kXcds;
+    if (blocks64 > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
+    const dim3 grid(static_cast<uint32_t>(blocks64)), block(kWave);
     if (a.dense_nontemporal) {
         switch (a.nbufs) {
         case 1: hipLaunchKernelGGL((shuffle_dense_kernel<1, true>), grid, block, lds_bytes, stream, a); break;
