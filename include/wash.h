@@ -20,8 +20,9 @@
  *   - "device" pointers are HIP device memory on the CURRENT device of the
  *     calling thread; "host" pointers are ordinary process memory.
  *   - The caller owns every buffer it passes.  The library allocates only a
- *     small internal device table per distinct segment list (cached, released
- *     by wash_shutdown()).
+ *     small internal device table per distinct segment list (cached) and one
+ *     1 MiB scratch buffer per device for wash_consensus_sqdist, on first use;
+ *     wash_shutdown() releases them.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls enqueue work on it and return without waiting; the usual stream
  *     ordering applies to the buffers.
