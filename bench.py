@@ -201,6 +201,7 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
         "graph_replay_ms_per_step": graph_ms,
         "avg_us": {k: v * 1e3 for k, v in avg_ms.items()},
         "median_us": {k: v * 1e3 for k, v in med_ms.items()},
+        "min_us": {k: min(tm.ms(k)) * 1e3 for k in avg_ms},
         "first_steps_us": {k: [round(x * 1e3, 1) for x in tm.ms(k)[:12]] for k in avg_ms},
         "shuffle_coords_per_s": P / (avg_ms["wash_shuffle"] * 1e-3),
         "shuffle_elements_per_s": selected * N * bufs / (avg_ms["wash_shuffle"] * 1e-3),
@@ -395,7 +396,7 @@ def main():
         "graph_replay_ms_per_step": main_res["graph_replay_ms_per_step"],
         "shuffle_coords_per_s": main_res["shuffle_coords_per_s"],
         "selected_per_step": main_res["selected_per_step"],
-        "kernel_us": main_res["avg_us"], "kernel_median_us": main_res["median_us"],
+        "kernel_us": main_res["avg_us"], "kernel_median_us": main_res["median_us"], "kernel_min_us": main_res["min_us"],
         "kernel_first_steps_us": main_res["first_steps_us"],
         "roofline": roofline,
         "roofline_per_kernel": {k: {kk: vv for kk, vv in v.items()} | {"traffic": load_traffic(workload_key, k)}
