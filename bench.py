@@ -1,16 +1,23 @@
 #!/usr/bin/env python3
 """Benchmark of the WASH population-update hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C] [--all-configs]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config C] [--headline-only]
 
 A "step" is one pass of the whole hot path over the population of the chosen
 workload: one wash_shuffle (thresholds, mask, permutation, gather-permute-
-scatter, plus momentum where the workload has it), one papa_ema (on its own
-copy of the population) and one wash_average.  Inputs are resident in HBM
-before the timed region; timing uses HIP events on the stream the kernels are
-launched on.  One JSON line is printed: headline value = coordinates per second of the whole
-pass; per-kernel times, algorithmic bytes and fractions of the 8 TB/s HBM peak; yardsticks (copy,
-scattered access); every config under all_configs; the CPU oracle timed on the same workload.
+scatter, plus momentum where the workload has it), one papa_ema and one
+wash_average.  The default workload is the largest configuration, N = 8 models
+of 1.1e9 parameters with momentum (70.4 GB resident in HBM).  Inputs are
+resident in HBM before the timed region; timing uses HIP events on the stream
+the kernels are launched on.
+
+The LAST line of stdout is one short JSON object: value = coordinates decided
+by wash_shuffle per second, ms_per_step = the whole pass, `roofline` for the
+kernel with the longest duration plus one entry per kernel, and the CPU oracle
+timed on a bounded sample of the same workload.  Everything else (per-kernel
+medians, yardsticks, every other configuration with both mask streams, the
+oracle timed on each configuration) goes to a side file, by default
+gpurun_out/bench_detail.json, and as progress lines to stderr.
 """
 import argparse
 import json
@@ -267,9 +274,26 @@ def scatter_yardstick(torch, wash, lines=1 << 25, blocks=8192, rounds=16):
     return out
 
 
-def cpu_baseline(cfg, budget_s=20.0):
-    """The oracle as it stands, single thread, on the same workload: whole passes
-    (shuffle + EMA + average) until about budget_s seconds of CPU work are spent."""
+def _r(x, digits=4):
+    """Round to `digits` significant digits (keeps the headline line short)."""
+    if x is None or x == 0:
+        return x
+    return float(f"{x:.{digits}g}")
+
+
+def bound_label(N, bufs, frac_selected, stream, dense):
+    """Which resource binds the shuffle kernel in this regime (measured: VALU activity, counters)."""
+    if dense:
+        return "hbm"                      # rows streamed through LDS: a plain in-place pass over the bytes
+    if frac_selected * N * bufs < 0.05:
+        # the Philox mask scan (one quarter call per coordinate) outweighs the scattered accesses
+        return "valu" if stream == "v1" else "latency"
+    return "hbm"
+
+
+def cpu_baseline_full(cfg, budget_s=3.0, mt_budget_s=0.5):
+    """The oracle as it stands on whole passes (shuffle + EMA + average) of a configuration that fits
+    the host: single thread, until about budget_s seconds are spent; then the shuffle alone over all cores."""
     import oracle
     from workloads import host_population
 
@@ -291,24 +315,79 @@ def cpu_baseline(cfg, budget_s=20.0):
         parts["wash_average"] += t3 - t2
         t_spent += t3 - t0
         passes += 1
-    # the oracle's shuffle also runs over all host cores (coordinates are independent and the stream is
-    # addressed by the coordinate, so the bits are the same); a few calls, reported beside the baseline
     threads = max(1, min(16, os.cpu_count() or 1))
     mt_calls, mt_spent = 0, 0.0
-    while mt_calls < 3 or (mt_spent < 2.0 and mt_calls < 50):
+    while mt_calls < 2 or (mt_spent < mt_budget_s and mt_calls < 50):
         t0 = time.perf_counter()
         oracle.shuffle(pop, mom, segs, cfg.seed, 1000 + mt_calls, threads=threads)
         mt_spent += time.perf_counter() - t0
         mt_calls += 1
     return {
-        "value": cfg.P * passes / t_spent, "unit": "coords/s", "cores": 1, "kind": "oracle",
-        "shuffle_all_cores": {"threads": threads, "us_per_call": mt_spent / mt_calls * 1e6, "calls": mt_calls},
-        "sample": f"{passes} whole passes (shuffle + EMA + average) over the full config-{cfg.index} population, "
-                  f"{t_spent:.1f} s of CPU time",
-        "ms_per_step": t_spent / passes * 1e3,
-        "us_per_call": {k: v / passes * 1e6 for k, v in parts.items()},
+        "value": _r(cfg.P * passes / parts["wash_shuffle"], 5), "unit": "coords/s", "cores": 1, "kind": "oracle",
+        "sample": f"{passes} whole passes over the full config-{cfg.index} population, {t_spent:.1f} s of CPU time",
+        "us_per_call": {k: round(v / passes * 1e6, 1) for k, v in parts.items()},
+        "shuffle_all_cores": {"threads": threads, "us_per_call": round(mt_spent / mt_calls * 1e6, 1),
+                              "coords_per_s": _r(cfg.P * mt_calls / mt_spent, 5)},
         "host_cores_available": os.cpu_count(),
     }
+
+
+def cpu_baseline_sampled(cfg, steps=3, nsample=3):
+    """The oracle on a bounded sample of a population that does not fit the host: whole tensor segments
+    (all N rows, parameters and momentum) at their true coordinates and probabilities, shuffled with the
+    oracle's window call, then EMA and average on the same columns; the per-coordinate cost is scaled to
+    the whole row.  Single thread, then the shuffle over all cores."""
+    import numpy as np
+    import oracle
+
+    segs = cfg.segments()
+    # three segments spread over the list (first, middle, last of those long enough to time)
+    long_enough = [s for s, (_, length, _) in enumerate(segs) if length >= 100_000]
+    sample_segments = sorted({long_enough[(len(long_enough) - 1) * k // (nsample - 1)] for k in range(nsample)})
+    rng = np.random.default_rng(cfg.data_seed)
+    threads = max(1, min(16, os.cpu_count() or 1))
+    parts = {"wash_shuffle": 0.0, "papa_ema": 0.0, "wash_average": 0.0}
+    coords, mt_spent, mt_coords = 0, 0.0, 0
+    for s in sample_segments:
+        off, length, p = segs[s]
+        win = (rng.standard_normal((cfg.N, length), dtype=np.float32) * np.float32(0.02))
+        mom = (rng.standard_normal((cfg.N, length), dtype=np.float32) * np.float32(1e-3)) if cfg.momentum else None
+        for step in range(steps):
+            t0 = time.perf_counter()
+            oracle.shuffle_window(win, mom, cfg.P, off, segs, cfg.seed, step)
+            t1 = time.perf_counter()
+            oracle.ema(win, cfg.alpha)
+            t2 = time.perf_counter()
+            oracle.average(win)
+            t3 = time.perf_counter()
+            parts["wash_shuffle"] += t1 - t0
+            parts["papa_ema"] += t2 - t1
+            parts["wash_average"] += t3 - t2
+            coords += length
+        # all cores: the same columns as a population of their own (same p, same amount of work)
+        for step in range(steps):
+            t0 = time.perf_counter()
+            oracle.shuffle(win, mom, [(0, length, p)], cfg.seed, step, threads=threads)
+            mt_spent += time.perf_counter() - t0
+            mt_coords += length
+    scale = cfg.P / coords                # per-coordinate cost of the sample, times the coordinates of a whole row
+    total = sum(parts.values())
+    return {
+        "value": _r(coords / parts["wash_shuffle"], 5), "unit": "coords/s", "cores": 1, "kind": "oracle",
+        "sample": f"{len(sample_segments)} of {len(segs)} segments ({coords // steps} coordinates x {cfg.N} rows, "
+                  f"params{'+momentum' if cfg.momentum else ''}) x {steps} steps, {total:.1f} s CPU; "
+                  "ms per call extrapolated to the whole row",
+        "extrapolated_ms_per_call": {k: round(v * scale * 1e3) for k, v in parts.items()},
+        "shuffle_all_cores": {"threads": threads, "coords_per_s": _r(mt_coords / mt_spent, 5)},
+        "host_cores_available": os.cpu_count(),
+    }
+
+
+def cpu_baseline(cfg, sample_steps=3, nsample=3):
+    host_bytes = cfg.N * cfg.P * 4 * (3 if cfg.momentum else 2)
+    if host_bytes > 4 * (1 << 30):
+        return cpu_baseline_sampled(cfg, steps=sample_steps, nsample=nsample)
+    return cpu_baseline_full(cfg)
 
 
 def load_traffic(workload_key, kernel):
@@ -329,14 +408,16 @@ def load_traffic(workload_key, kernel):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="1..5 (default 2: ResNet-18, N=5, p=0.001)")
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=5,
+                    help="1..5 (default 5: N=8 models x 1.1e9 parameters with momentum, the largest single-GPU workload)")
     ap.add_argument("--p", type=float, default=None, help="override the shuffle probability of every tensor")
-    ap.add_argument("--all-configs", action="store_true", help="(default behaviour, kept for compatibility)")
-    ap.add_argument("--skip-all-configs", action="store_true",
-                    help="time only the headline workload; by default every config (and both shuffle streams) "
-                         "is also timed with at most 20 steps each and reported under 'all_configs'")
+    ap.add_argument("--headline-only", "--skip-all-configs", dest="headline_only", action="store_true",
+                    help="time only the headline workload; by default the other configs (both shuffle streams, the "
+                         "oracle beside each) are timed too, with at most 20 steps each, into the detail file")
+    ap.add_argument("--detail", default=os.path.join(ROOT, "gpurun_out", "bench_detail.json"),
+                    help="side file for everything that does not fit the headline line ('' = none)")
     ap.add_argument("--stream", choices=["v1", "gap"], default="v1",
                     help="mask stream of the shuffle: v1 = wash_shuffle, gap = wash_shuffle_gap")
     ap.add_argument("--states", type=int, default=None, choices=[1, 2, 3, 4],
@@ -383,78 +464,117 @@ def main():
         print(json.dumps({"copy_yardstick": copy_yardstick(torch, wash)}))
         return
 
+    def note(msg):
+        print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
     cfg = get_config(args.config)
+    note(f"headline workload: config {cfg.index} ({cfg.name}), N={cfg.N}, P={cfg.P}")
     main_res = run_config(torch, wash, cfg, args.steps, args.warmup, p_override=args.p, count=not args.no_count,
                           stream=args.stream, states=args.states)
+    note(f"config {cfg.index}: shuffle {main_res['avg_us']['wash_shuffle']:.1f} us, ema "
+         f"{main_res['avg_us']['papa_ema']:.1f} us, average {main_res['avg_us']['wash_average']:.1f} us")
     yard = copy_yardstick(torch, wash)
     scat = scatter_yardstick(torch, wash)
 
     roof = main_res["roofline"]
-    dominant = max(roof, key=lambda k: roof[k]["avg_us"])
     workload_key = f"config{cfg.index}" + (f"_p{args.p:g}" if args.p is not None else "")
+    dense = args.p is not None and args.p >= 0.08 and args.stream == "v1"
+    shuffle_bound = bound_label(cfg.N, main_res["buffers_shuffled"], main_res["expected_fraction"], args.stream, dense)
+    per_kernel = {}
+    for k, v in roof.items():
+        traffic = load_traffic(workload_key, k)
+        e = {"us": _r(v["avg_us"]), "GBps": _r(v["achieved"]), "frac": _r(v["frac"], 3),
+             "bound": shuffle_bound if k == "wash_shuffle" else "hbm", "traffic": traffic}
+        if traffic:
+            # counted HBM bytes over the kernel time: what the memory system actually moved
+            e["traffic_frac"] = _r(traffic / (v["avg_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 3)
+        per_kernel[k] = e
+    dominant = max(roof, key=lambda k: roof[k]["avg_us"])
     r = roof[dominant]
-    roofline = {"kernel": dominant, "bound": "hbm", "achieved": r["achieved"], "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": r["frac"], "traffic": load_traffic(workload_key, dominant),
-                "alg_bytes_per_launch": r["alg_bytes"], "avg_us": r["avg_us"]}
+    roofline = {"kernel": dominant, "bound": per_kernel[dominant]["bound"], "achieved": _r(r["achieved"]),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": _r(r["frac"], 3),
+                "traffic": per_kernel[dominant]["traffic"], "traffic_frac": per_kernel[dominant].get("traffic_frac"),
+                "alg_bytes_per_launch": _r(r["alg_bytes"], 5), "avg_us": _r(r["avg_us"])}
 
+    roofline["traffic"] = per_kernel[dominant]["traffic"]
+    for e in per_kernel.values():
+        e.pop("traffic")
+    cpu = None
+    if not args.no_cpu_baseline:
+        note("timing the CPU oracle on the headline workload")
+        cpu = cpu_baseline(cfg, sample_steps=10, nsample=9)
+        note(f"oracle: {cpu['value']:.3g} coords/s on one core")
+
+    p_text = f"p={args.p:g}" if args.p is not None else (
+        "p linear 0.05->0.001 over 200 segments" if cfg.index == 5 else f"p={cfg.probs(1)[0]:g}")
     line = {
         "metric": "shuffle coords/s + effective HBM GB/s (% of roofline) at N models x P params",
-        "value": main_res["pass_coords_per_s"], "unit": "coords/s",
+        "value": _r(main_res["shuffle_coords_per_s"], 5), "unit": "coords/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f64", "storage_dtype": "f32 (shuffle moves raw 32-bit words)", "data": "synthetic",
-        "config": {"workload": f"config {cfg.index}: {cfg.name}, N={cfg.N}, P={cfg.P}, "
-                               f"{main_res['segments']} tensors, p={args.p if args.p is not None else 'as listed'}, "
-                               f"{'params+momentum' if cfg.momentum else 'params only'}; "
-                               "step = wash_shuffle + papa_ema + wash_average",
-                   "N": cfg.N, "P": cfg.P, "cache_resident": main_res["cache_resident"]},
-        "graph_replay_ms_per_step": main_res["graph_replay_ms_per_step"],
-        "shuffle_coords_per_s": main_res["shuffle_coords_per_s"],
+        "ms_per_step": _r(main_res["ms_per_step"], 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config {cfg.index}: {cfg.name}, N={cfg.N}, P={cfg.P}, {p_text}, "
+                               f"{'params+momentum' if cfg.momentum else 'params only'}, "
+                               f"{main_res['population_bytes'] / 1e9:.1f} GB in HBM; step = wash_shuffle + papa_ema + "
+                               "wash_average; value = P / wash_shuffle time"},
+        "pass_coords_per_s": _r(main_res["pass_coords_per_s"], 5),
         "selected_per_step": main_res["selected_per_step"],
-        "kernel_us": main_res["avg_us"], "kernel_median_us": main_res["median_us"], "kernel_min_us": main_res["min_us"],
-        "kernel_cold_cache_us": main_res["cold_cache_us"],
-        "kernel_first_steps_us": main_res["first_steps_us"],
         "roofline": roofline,
-        "roofline_per_kernel": {k: {kk: vv for kk, vv in v.items()} | {"traffic": load_traffic(workload_key, k)}
-                                for k, v in roof.items()},
-        "analysis_passes": main_res["analysis_passes"],
-        "copy_yardstick": yard,
-        "scatter_yardstick": scat,
-        "shuffle_elements_per_s": main_res["shuffle_elements_per_s"],
-        # every moved value needs a scattered store: expected distinct 64-byte half lines written per second,
-        # against the measured rate of scattered stores (the shuffle's practical ceiling once the population is
-        # large and p is high enough for the writes to outweigh the mask scan; from p = 0.08 the library streams
-        # whole rows instead of scattering, and this ratio no longer bounds anything)
-        "shuffle_vs_scattered_stores": {
-            "bound": "scattered-store", "achieved": main_res["shuffle_store_units_per_s"] / 1e9,
-            "peak": scat["stores_Gelem_per_s"], "unit": "G half-lines/s",
-            "frac": main_res["shuffle_store_units_per_s"] / (scat["stores_Gelem_per_s"] * 1e9)},
+        "roofline_per_kernel": per_kernel,
+        "cpu_baseline": cpu,
     }
 
-    headline_only = args.skip_all_configs or args.config != 2 or args.p is not None or args.stream != "v1" or args.states is not None
-    if not headline_only or args.all_configs:
+    detail = {"headline": line, "headline_detail": main_res, "copy_yardstick": yard, "scatter_yardstick": scat,
+              "shuffle_vs_scattered_stores": {
+                  "bound": "scattered-store", "achieved": main_res["shuffle_store_units_per_s"] / 1e9,
+                  "peak": scat["stores_Gelem_per_s"], "unit": "G half-lines/s",
+                  "frac": main_res["shuffle_store_units_per_s"] / (scat["stores_Gelem_per_s"] * 1e9)}}
+
+    default_run = (args.p is None and args.stream == "v1" and args.states is None)
+    if not args.headline_only and default_run:
         rows = []
         for c in CONFIGS:
             ps = c.p_sweep if c.p_sweep else (None,)
             for p in ps:
-                k = max(5, min(args.steps, c.steps, 20))
+                k = max(5, min(c.steps, 20))
                 for st in ("v1", "gap"):
-                    res = run_config(torch, wash, c, k, min(args.warmup, 3), p_override=p, stream=st)
+                    if c.index == cfg.index and st == args.stream:
+                        res = dict(main_res)
+                    else:
+                        res = run_config(torch, wash, c, k, min(args.warmup, 3), p_override=p, stream=st)
                     res["p_override"] = p
+                    is_dense = st == "v1" and (p if p is not None else 0.0) >= 0.08
+                    res["roofline"]["wash_shuffle"]["bound"] = bound_label(c.N, res["buffers_shuffled"],
+                                                                           res["expected_fraction"], st, is_dense)
                     res["shuffle_vs_scattered_stores_frac"] = (res["shuffle_store_units_per_s"]
                                                                / (scat["stores_Gelem_per_s"] * 1e9))
                     rows.append(res)
-                    print(f"[bench] config {c.index} p={p} stream {st} done: shuffle "
-                          f"{res['avg_us']['wash_shuffle']:.1f} us, ema {res['avg_us']['papa_ema']:.1f} us, "
-                          f"avg {res['avg_us']['wash_average']:.1f} us", file=sys.stderr, flush=True)
-        line["all_configs"] = rows
+                    note(f"config {c.index} p={p} stream {st}: shuffle {res['avg_us']['wash_shuffle']:.1f} us "
+                         f"({res['roofline']['wash_shuffle']['frac'] * 100:.2f} % of 2pNP4/t, "
+                         f"{res['roofline']['wash_shuffle']['bound']}-bound), ema {res['avg_us']['papa_ema']:.1f} us "
+                         f"({res['roofline']['papa_ema']['frac'] * 100:.1f} %), average "
+                         f"{res['avg_us']['wash_average']:.1f} us ({res['roofline']['wash_average']['frac'] * 100:.1f} %)")
+        detail["all_configs"] = rows
+        if not args.no_cpu_baseline:
+            per_cfg = {}
+            for c in CONFIGS:
+                per_cfg[f"config{c.index}"] = cpu if c.index == cfg.index else cpu_baseline(c)
+                b = per_cfg[f"config{c.index}"]
+                note(f"oracle, config {c.index}: {b['value']:.3g} coords/s (1 core), "
+                     f"{b['shuffle_all_cores']['coords_per_s']:.3g} coords/s ({b['shuffle_all_cores']['threads']} threads)")
+            detail["cpu_baseline_per_config"] = per_cfg
 
-    if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(cfg)
-    else:
-        line["cpu_baseline"] = None
+    if args.detail:
+        try:
+            os.makedirs(os.path.dirname(args.detail), exist_ok=True)
+            with open(args.detail, "w") as f:
+                json.dump(detail, f, indent=1)
+            line["detail_file"] = os.path.relpath(args.detail, ROOT)
+        except OSError as exc:
+            note(f"detail file not written: {exc}")
 
-    print(json.dumps(line), flush=True)
+    sys.stderr.flush()
+    print(json.dumps(line, separators=(",", ":")), flush=True)
 
 
 if __name__ == "__main__":
