@@ -116,6 +116,8 @@ int wash_shuffle(float *params, float *momentum, uint32_t N, uint64_t P,
  * work is then proportional to the number of SELECTED coordinates, p * P per
  * step, the quantity the paper counts as communication volume (Sec. 3), instead
  * of P.  The permutation of a selected coordinate is the one of wash_shuffle.
+ * A segment whose p is so small that 1 - p rounds to 1 in double (p <= 2^-54)
+ * selects nothing, like p = 0: Bernoulli(p) to within 2^-54 per coordinate.
  * Results differ bit for bit from wash_shuffle (different mask), are the same
  * in law, and are a pure function of (seed, step, N, and the segment list after
  * dropping empty segments and merging touching neighbours of equal p).

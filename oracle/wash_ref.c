@@ -245,7 +245,11 @@ int wash_shuffle_ref(float *params, float *momentum, uint32_t N, uint64_t P,
  *
  * Definition (this repository's own; the paper fixes the law only):
  *   - zero-length segments are dropped and neighbours that touch and have the
- *     same p (same double) are merged; segments with p = 0 select nothing;
+ *     same p (same double) are merged; segments with p = 0 select nothing, and
+ *     neither do segments whose p is so small that 1 - p rounds to 1 in double
+ *     (p <= 2^-54: log2(1 - p) would be 0 and the inversion meaningless; the
+ *     Bernoulli(p) law of Eq. 3 is then met to within 2^-54 per coordinate,
+ *     far inside the 2^-33 of the other stream's threshold);
  *   - a merged segment [a, b) is cut into pieces [s, e) at the multiples of 1024;
  *   - in a piece, pos = s - 1; for d = 0, 1, 2, ...:
  *       U_d  = the top 53 bits of the 64-bit number (hi = word 2(d mod 2),
@@ -312,8 +316,9 @@ uint64_t wash_ref_gap_uniform(uint64_t seed, uint64_t step, uint64_t s, uint32_t
 uint32_t wash_ref_gap(uint64_t U, double inv)
 {
     double L = wash_ref_log2((double)(U + 1u)) - 53.0; /* log2 of u = (U+1)/2^53, in [-53, 0] */
-    double q = L * inv;                                /* >= 0 */
-    if (!(q < 2047.0)) q = 2047.0;
+    double q = L * inv;                                /* >= 0 for the inv of a probability */
+    if (!(q < 2047.0)) q = 2047.0;                     /* also NaN */
+    if (q < 0.0) q = 0.0;
     return 1u + (uint32_t)floor(q);
 }
 
@@ -336,7 +341,7 @@ static void gap_walk(uint64_t g_begin, uint64_t g_end, const wash_ref_segment *s
             if (segs[k].length != 0) b = segs[k].offset + segs[k].length;
             ++k;
         }
-        if (p == 0.0) continue;
+        if (p == 0.0 || 1.0 - p == 1.0) continue;
         double inv = wash_ref_gap_scale(p);
 
         for (uint64_t s = a; s < b; ) {

@@ -274,7 +274,7 @@ static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t
         for (const wash::DevSegment &d : active) {
             double pval;
             std::memcpy(&pval, &d.param, sizeof(pval));
-            if (pval == 0.0) continue;
+            if (wash::gap_never_selects(pval)) continue;
             if (pval > p_max) p_max = pval;
             const double scale = wash::gap_scale(pval);
             wash::DevSegment out = d;

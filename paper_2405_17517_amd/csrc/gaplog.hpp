@@ -43,7 +43,11 @@ __host__ __device__ inline double gap_log2(double x)
     return static_cast<double>(e) + ln_m * 1.4426950408889634;
 }
 
-// 1 / log2(1-p) for 0 < p < 1; 0 for p = 1 (every distance is 1).
+// A probability so small that 1 - p rounds to 1 has no usable log2(1 - p): such a segment selects
+// nothing (the Bernoulli(p) law of Eq. 3 is then met to within 2^-54 per coordinate).
+inline bool gap_never_selects(double p) { return p == 0.0 || 1.0 - p == 1.0; }
+
+// 1 / log2(1-p) for 2^-54 < p < 1; 0 for p = 1 (every distance is 1).
 inline double gap_scale(double p)
 {
     if (p >= 1.0) return 0.0;
@@ -54,8 +58,9 @@ inline double gap_scale(double p)
 __device__ __forceinline__ uint32_t gap_distance(uint64_t U, double scale)
 {
     const double L = gap_log2(static_cast<double>(U + 1u)) - 53.0;   // log2 of (U+1)/2^53, in [-53, 0]
-    double q = L * scale;                                            // >= 0
-    if (!(q < 2047.0)) q = 2047.0;
+    double q = L * scale;                                            // >= 0 for the scale of a probability
+    if (!(q < 2047.0)) q = 2047.0;                                   // also NaN
+    if (q < 0.0) q = 0.0;
     return 1u + static_cast<uint32_t>(q);
 }
 

@@ -150,6 +150,21 @@ def test_gap_equal_p_neighbours_merge_and_p1_matches_v1(wash):
     assert a[2] == b[2] == P and np.array_equal(_bits(a[0]), _bits(b[0]))
 
 
+def test_gap_probabilities_below_double_resolution(wash):
+    """Segments whose p is so small that 1 - p rounds to 1 select nothing (Bernoulli(p) of Eq. 3), alone
+    and between ordinary segments, whose streams they leave alone."""
+    N, P = 6, 40_000
+    pop = distinct_population(N, P)
+    for segs in ([(0, P, 1e-17)], [(0, P, 5e-324)], [(0, 100, 2.0 ** -54), (100, P - 100, 1e-300)],
+                 [(0, 3000, 0.05), (3000, 2000, 1e-300), (5000, 30_000, 0.05), (35_000, 5000, 2.0 ** -53)]):
+        ref = pop.copy()
+        ref_cnt = oracle.shuffle(ref, None, segs, 13, 2, stream="gap")
+        got, _, cnt = _run_shuffle(wash, pop, None, segs, 13, 2, stream="gap")
+        assert cnt == ref_cnt and np.array_equal(_bits(got), _bits(ref)), segs
+        if max(p for _, _, p in segs) < 1e-10:
+            assert cnt == 0 and np.array_equal(_bits(got), _bits(pop))
+
+
 def test_shuffle_is_deterministic_and_tile_independent(wash):
     N, P = 10, 1 << 18
     pop = distinct_population(N, P)
@@ -195,6 +210,13 @@ def test_shuffle_keeps_mean_and_multiset_on_device(wash):
     # the sum is taken in ascending n, so a permuted column may round differently in fp64;
     # after rounding to fp32 that is below the 1e-6 bar by orders of magnitude
     assert torch.allclose(after, before, rtol=1e-6, atol=1e-9)
+    # and against the oracle: the shuffled population bit for bit, its average within the bar
+    ref = pop.copy()
+    oracle.shuffle(ref, None, [(0, P, 0.1)], 8, 0, threads=8)
+    assert np.array_equal(_bits(d.cpu().numpy()), _bits(ref))
+    ref_avg = oracle.average(ref)
+    scale = np.maximum(np.abs(ref_avg), np.abs(ref).mean(axis=0))
+    assert np.all(np.abs(after.cpu().numpy() - ref_avg) <= 1e-6 * scale)
 
 
 def test_error_paths_launch_nothing(wash):

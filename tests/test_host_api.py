@@ -93,6 +93,14 @@ def test_validation_happens_before_any_gpu_call(lib):
     assert b"step_dev" in lib.wash_last_error_detail()
     assert lib.wash_shuffle_device_step(ctypes.addressof(two), 2, 2, 10, None, 0, 0, far, 1, 0, far, None) == -1
     assert lib.wash_shuffle_device_step(ctypes.addressof(two), 5, 2, 10, None, 0, 0, far, 1, 0, None, None) == -1
+    # a list that can select nothing (p = 0, or p below the resolution of 1 - p on the gap stream) returns
+    # before any device is touched
+    lib.wash_shuffle_gap.argtypes = [vp, vp, u32, u64, vp, u32, u64, u64, vp, vp]
+    segs = (oracle.Segment * 3)()
+    for k, (off, ln, p) in enumerate([(0, 4, 0.0), (4, 3, 1e-17), (7, 3, 2.0 ** -54)]):
+        segs[k].offset, segs[k].length, segs[k].p = off, ln, p
+    assert lib.wash_shuffle_gap(4096, None, 2, 10, ctypes.addressof(segs), 3, 0, 0, None, None) == 0
+    assert lib.wash_shuffle(4096, None, 2, 10, ctypes.addressof(segs), 3, 0, 0, None, None) == 0   # thresholds round to 0
     assert lib.wash_average(None, 4096, 2, 10, None) == -1
     assert lib.wash_average(4096, None, 2, 10, None) == -1
     assert lib.wash_average(4096, 4100, 2, 10, None) == -1                          # out overlaps params

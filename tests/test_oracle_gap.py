@@ -39,6 +39,8 @@ def _py_gap(U, inv):
     q = (_py_log2(float(U + 1)) - 53.0) * inv
     if not q < 2047.0:
         q = 2047.0
+    if q < 0.0:
+        q = 0.0
     return 1 + int(math.floor(q))
 
 
@@ -58,7 +60,7 @@ def _py_mask(P, segs, seed, step):
             merged.append([off, off + ln, p])
     sel = []
     for a, b, p in merged:
-        if p == 0.0:
+        if p == 0.0 or 1.0 - p == 1.0:
             continue
         inv = 0.0 if p >= 1.0 else 1.0 / _py_log2(1.0 - p)
         s = a
@@ -212,6 +214,48 @@ def test_p1_equals_stream_v1_and_p0_is_identity():
     c = pop.copy()
     assert oracle.shuffle(c, None, [(0, 5000, 0.0)], 4, 2, stream="gap") == 0
     assert np.array_equal(_bits(c), _bits(pop))
+
+
+def test_probabilities_below_double_resolution_select_nothing():
+    """Bernoulli(p) of Eq. 3 for p so small that 1 - p rounds to 1: log2(1 - p) is 0 there and a naive
+    inversion would select EVERY coordinate; the law asks for (almost surely) none."""
+    P = 1 << 16
+    pop = distinct_population(4, P)
+    for p in (5e-324, 1e-300, 1e-17, 2.0 ** -54):
+        assert 1.0 - p == 1.0
+        for seed in (0, 7):
+            assert not oracle.gap_mask(P, [(0, P, p)], seed, 3).any()
+            a = pop.copy()
+            assert oracle.shuffle(a, None, [(0, P, p)], seed, 3, stream="gap") == 0
+            assert np.array_equal(_bits(a), _bits(pop))
+    # the smallest probabilities that still have a logarithm: the walk runs, and selects with probability
+    # about p per coordinate (P * p < 1e-11 here, so nothing is selected either)
+    for p in (2.0 ** -53, 1.2e-16, 1e-15):
+        assert 1.0 - p != 1.0 and math.isfinite(oracle.gap_scale(p))
+        assert not oracle.gap_mask(P, [(0, P, p)], 1, 0).any()
+    # a tiny-p segment between two ordinary ones leaves their streams alone (pieces restart at segment starts)
+    segs = [(0, 3000, 0.05), (3000, 2000, 1e-300), (5000, 3000, 0.05)]
+    m = oracle.gap_mask(8000, segs, 5, 1)
+    assert not m[3000:5000].any() and m[:3000].any() and m[5000:].any()
+    assert np.array_equal(m[:3000], oracle.gap_mask(8000, [(0, 3000, 0.05)], 5, 1)[:3000])
+    assert np.array_equal(m[5000:], oracle.gap_mask(8000, [(5000, 3000, 0.05)], 5, 1)[5000:])
+    # the distance is defined for any scale, also the degenerate ones (no undefined conversion)
+    inf = float("inf")
+    assert oracle.gap(12345, -inf) == 2048 and oracle.gap(2 ** 53 - 1, -inf) == 2048
+    assert oracle.gap(12345, inf) == 1 and oracle.gap(12345, float("nan")) == 2048
+
+
+def test_log2_against_libm_dense_sample():
+    """The stream's log2 against the C library's on a dense sample, as a RELATIVE error (also just
+    below 1, where the result is tiny and log2(1 - p) of a small p lives): a wrong series coefficient
+    or constant cannot hide behind an absolute tolerance."""
+    rng = np.random.default_rng(11)
+    xs = np.concatenate([rng.uniform(0.5, 2.0, 20000),
+                         1.0 - rng.uniform(0.5, 1.0, 20000) * 2.0 ** -rng.integers(1, 50, 20000).astype(np.float64),
+                         rng.integers(1, 2 ** 53, 20000).astype(np.float64)])
+    for x in xs:
+        ref = math.log2(float(x))
+        assert abs(oracle.log2(float(x)) - ref) <= 4.5e-16 * abs(ref), x
 
 
 def test_invariants_momentum_threads_windows_segmentation():

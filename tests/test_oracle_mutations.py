@@ -129,6 +129,7 @@ def _pin_gap_stream():
     assert np.array_equal(one, m.astype(np.uint8))               # touching equal-p segments merge
     segs = [(0, 100, 0.5), (100, 900, 0.5), (1000, 24, 0.5), (1030, 3000, 0.02), (4030, 66, 1.0), (5096, 1900, 0.3)]
     assert list(np.flatnonzero(oracle.gap_mask(7000, segs, 5, 9))) == _py_mask(7000, segs, 5, 9)   # Python twin
+    assert not oracle.gap_mask(4096, [(0, 4096, 1e-17)], 3, 1).any()    # 1 - p rounds to 1: Bernoulli(p) selects nothing
     a1 = np.repeat(np.arange(4, dtype=np.float32)[:, None], 2000, axis=1).copy()
     b1 = a1.copy()
     oracle.shuffle(a1, None, [(0, 2000, 1.0)], 4, 2, stream="gap")
@@ -183,6 +184,7 @@ MUTATIONS = [
     ("gap: second draw reuses the first words", "out[2u * (d & 1u)] << 32) | (uint64_t)out[2u * (d & 1u) + 1u]", "out[0] << 32) | (uint64_t)out[1]"),
     ("gap: log of p instead of 1-p", "return 1.0 / wash_ref_log2(1.0 - p);", "return 1.0 / wash_ref_log2(p);"),
     ("gap: no restart at 1024", "uint64_t e = (s / WASH_REF_PIECE + 1u) * WASH_REF_PIECE;", "uint64_t e = (s / 4096u + 1u) * 4096u;"),
+    ("gap: probabilities below double resolution select everything", "if (p == 0.0 || 1.0 - p == 1.0) continue;", "if (p == 0.0) continue;"),
     ("gap: touching equal-p segments not merged", "(segs[k].offset == b && segs[k].p == p)", "(0)"),
 ]
 
