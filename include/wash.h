@@ -212,6 +212,24 @@ int wash_consensus_sqdist(const float *params, uint32_t N, uint64_t P,
                           uint64_t g_begin, uint64_t g_end, double *out, void *stream);
 
 /*
+ * wash_consensus_sqdist for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same kernels, same result bit for bit; the partial sums go to
+ * a fixed 1 MiB array in the library's device image instead of an allocated
+ * buffer, so the call makes no hipMalloc / hipFree and calls no allocating
+ * routine (the first call on a device looks up the array's address there).
+ * Limits: N <= WASH_MAX_N and P <= 2^40, which is all the fixed array has to
+ * cover (at most 4096 blocks x 32 partial sums); anything larger is WASH_EINVAL
+ * as in wash_consensus_sqdist.  Every GPU the library runs on holds its own copy
+ * of the array until the process ends.  All calls on one GPU share that copy:
+ * two calls that overlap there (different streams) race on it and may return
+ * wrong sums; calls on one stream are ordered and safe.  Nothing in the array
+ * has to start at zero (every slot a launch reads, it has written first).
+ */
+int wash_consensus_sqdist_noalloc(const float *params, uint32_t N, uint64_t P,
+                                  uint64_t g_begin, uint64_t g_end, double *out, void *stream);
+
+/*
  * Weighted combination of the models: out[g] = sum_n weights[n] * params[n][g],
  * products and sum in fp64 in ascending n, rounded once to fp32.  Convex
  * weights give the interpolations studied in the appendix; a 0/1-over-k vector

@@ -50,6 +50,8 @@ def _load():
     L.papa_ema.restype = ctypes.c_int
     L.wash_consensus_sqdist.argtypes = [vp, u32, u64, u64, u64, vp, vp]
     L.wash_consensus_sqdist.restype = ctypes.c_int
+    L.wash_consensus_sqdist_noalloc.argtypes = [vp, u32, u64, u64, u64, vp, vp]
+    L.wash_consensus_sqdist_noalloc.restype = ctypes.c_int
     L.wash_weighted_average.argtypes = [vp, vp, vp, u32, u64, vp]
     L.wash_weighted_average.restype = ctypes.c_int
     L.wash_probe_scattered.argtypes = [vp, u64, ctypes.c_int, u32, u32, vp]
@@ -221,6 +223,22 @@ def wash_consensus_sqdist(params: torch.Tensor, g_begin: int = 0, g_end: Optiona
         rc = _lib.wash_consensus_sqdist(params.data_ptr(), N, P, int(g_begin), int(g_end), out.data_ptr(),
                                         _stream(params))
     _check(rc, "wash_consensus_sqdist")
+    return out
+
+
+def wash_consensus_sqdist_noalloc(params: torch.Tensor, out: torch.Tensor, g_begin: int = 0,
+                                  g_end: Optional[int] = None) -> torch.Tensor:
+    """wash_consensus_sqdist without any allocation: the caller brings out (float64 [N]); see wash.h."""
+    N, P = _dev_pop(params, "params")
+    if g_end is None:
+        g_end = P
+    if not (isinstance(out, torch.Tensor) and out.is_cuda and out.dtype == torch.float64 and out.is_contiguous()
+            and out.numel() == N and out.device == params.device):
+        raise TypeError("out: need a contiguous float64 [N] tensor on the same GPU")
+    with torch.cuda.device(params.device):
+        rc = _lib.wash_consensus_sqdist_noalloc(params.data_ptr(), N, P, int(g_begin), int(g_end), out.data_ptr(),
+                                                _stream(params))
+    _check(rc, "wash_consensus_sqdist_noalloc")
     return out
 
 

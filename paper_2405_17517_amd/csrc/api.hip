@@ -484,6 +484,28 @@ int wash_consensus_sqdist(const float *params, uint32_t N, uint64_t P, uint64_t 
     return WASH_OK;
 }
 
+int wash_consensus_sqdist_noalloc(const float *params, uint32_t N, uint64_t P, uint64_t g_begin, uint64_t g_end,
+                                  double *out, void *stream)
+{
+    g_detail[0] = 0;
+    if (int rc = check_population(params, N, P)) return rc;      // N <= 32 and P <= 2^40 are what the fixed scratch covers
+    if (out == nullptr) return fail(WASH_EINVAL, "out is NULL");
+    if (g_begin > g_end || g_end > P) return fail(WASH_EINVAL, "slice outside [0,P]");
+    if (ranges_overlap(params, static_cast<uint64_t>(N) * P * sizeof(float), out, N * sizeof(double)))
+        return fail(WASH_EINVAL, "out overlaps params");
+    static_assert(static_cast<size_t>(wash::kSqdistMaxBlocks) * WASH_MAX_N * sizeof(double) <= wash::kSqdistScratchBytes,
+                  "the fixed scratch must hold the partial sums of the largest launch");
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return fail_hip("hipGetDevice", e);
+    double *partial = nullptr;
+    e = wash::static_sqdist_scratch(device, &partial);
+    if (e != hipSuccess) return fail_hip("hipGetSymbolAddress(scratch)", e);
+    e = wash::launch_sqdist(params, N, P, g_begin, g_end, partial, out, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip("wash_consensus_sqdist_noalloc launch", e);
+    return WASH_OK;
+}
+
 int wash_weighted_average(const float *params, const double *weights, float *out, uint32_t N, uint64_t P,
                           void *stream)
 {

@@ -6,12 +6,23 @@
 //                      models (interpolation study, soups); fp64, rounded once
 #include "kernels.hpp"
 
+#include <mutex>
+
 namespace wash {
 
 namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWave = 64;
+
+// Partial sums of wash_consensus_sqdist_noalloc: fixed device storage, so that the call allocates
+// nothing.  Every GPU the library runs on holds its own copy, at its own address, until the process
+// ends.  In host code this name is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[kSqdistScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+double *g_scratch_ptr[kMaxDevices] = {};     // per device: address of that device's copy of `scratch`
 
 typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
 
@@ -203,6 +214,22 @@ hipError_t run_sqdist(const float *params, uint64_t P, uint64_t g_begin, uint64_
 }
 
 }  // namespace
+
+// Address of the CURRENT device's copy of the static scratch array (looked up once per device).
+hipError_t static_sqdist_scratch(int device, double **out)
+{
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[device] == nullptr) {
+        void *ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (ptr == nullptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = static_cast<double *>(ptr);
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
 
 uint32_t sqdist_blocks(uint64_t span)
 {

@@ -64,6 +64,8 @@ hipError_t launch_weighted_average(const float *params, float *out, uint32_t N, 
 constexpr uint32_t kSqdistMaxBlocks = 4096;
 constexpr size_t kSqdistScratchBytes = static_cast<size_t>(kSqdistMaxBlocks) * 32 * sizeof(double);
 uint32_t sqdist_blocks(uint64_t span);
+// the current device's copy of a file-scope device array of kSqdistScratchBytes (no allocation)
+hipError_t static_sqdist_scratch(int device, double **out);
 hipError_t launch_sqdist(const float *params, uint32_t N, uint64_t P, uint64_t g_begin, uint64_t g_end,
                          double *partial, double *out, hipStream_t stream);
 
