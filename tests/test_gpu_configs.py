@@ -1,13 +1,11 @@
 """GPU parity at the full sizes of the five benchmark configurations, in the
 launch configuration bench.py times (default tile choice, count requested).
 
-Configs 1-4 are compared element by element over the whole population.  Config
-5 (70 GB with momentum) does not fit next to an oracle copy on the host, so it
-is compared on sampled column windows (the stream is addressed by the global
-coordinate, so the oracle can shuffle a window on its own) and, over the whole
-population, through properties that hold at any size: per-coordinate XOR and
-wrapping sum of the N bit patterns are unchanged, and the selected count lies
-in the binomial band around sum_s p_s * len_s."""
+All five configs are compared element by element over the whole population:
+configs 1-4 against an oracle copy on the host, config 5 (70 GB with momentum)
+chunk by chunk against a device copy of its initial state (the stream is
+addressed by the global coordinate, so the oracle can shuffle a window on its
+own)."""
 import math
 import os
 
@@ -99,69 +97,90 @@ def test_config4_vit_p_sweep(wash, stream):
 
 
 @pytest.mark.parametrize("stream", STREAMS)
-def test_config5_stress_windows_and_invariants(wash, stream):
+def test_config5_whole_population(wash, stream):
+    """Config 5 (N = 8, P = 1.1e9, params + momentum, 10 steps, then average and EMA) compared with the
+    oracle on EVERY coordinate.  The 70 GB population cannot sit beside an oracle copy on the host, so a
+    device copy of the initial state is kept (5 x 35 GB on the device in all) and the row is walked in
+    chunks of 2^20 columns: initial and final chunks are downloaded, the oracle replays all steps on the
+    initial chunk (its stream is addressed by the global coordinate), and parameters, momentum, the
+    average and the EMA of the chunk are compared; the selected count must equal the oracle's."""
+    from concurrent.futures import ThreadPoolExecutor
+
     shuffle = wash.wash_shuffle if stream == "v1" else wash.wash_shuffle_gap
     cfg = get_config(5)
-    N, P = cfg.N, cfg.P
+    N, P, steps, alpha = cfg.N, cfg.P, cfg.steps, cfg.alpha
     segs_list = cfg.segments()
     segs = wash.SegmentList(segs_list)
     pop, mom = device_population(cfg.tensors(), N, cfg.init, cfg.data_seed, True)
-    print("config 5 generated", flush=True)
-
-    def fold(t):
-        """per-coordinate XOR and wrapping sum over the N rows, as int32 [P] each."""
-        x = torch.zeros(P, dtype=torch.int32, device="cuda")
-        s = torch.zeros(P, dtype=torch.int32, device="cuda")
-        v = t.view(torch.int32)
-        for n in range(N):
-            x.bitwise_xor_(v[n])
-            s.add_(v[n])
-        return x, s
-
-    fx, fs = fold(pop)
-    mx, ms = fold(mom)
-
-    W = 1 << 20
-    seg_len = segs_list[0][1]
-    starts = [0, P - W, seg_len - W // 2, 57 * seg_len - 12345, 199 * seg_len - W + 7, 4096 * 1000 - 3,
-              (P // 2 // 4096) * 4096 - W // 2, 123_456_789]
-    if stream == "gap":          # the oracle walks whole 1024-blocks: windows sit on that grid
-        starts = sorted({g0 // 1024 * 1024 for g0 in starts})
-    widths = [min(W, P - g0) if g0 + W + 1024 < P else P - g0 for g0 in starts]
-    init = [(pop[:, g0:g0 + w].clone(), mom[:, g0:g0 + w].clone()) for g0, w in zip(starts, widths)]
+    pop0, mom0 = pop.clone(), mom.clone()
+    print(f"config 5 generated, stream {stream}", flush=True)
 
     cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
-    steps = cfg.steps
     for step in range(steps):
         shuffle(pop, mom, segs, cfg.seed, step, cnt)
+    avg = wash.wash_average(pop)
+    ema = pop.clone()
+    wash.papa_ema(ema, alpha)
     torch.cuda.synchronize()
-    print("config 5 shuffled", flush=True)
+    print("config 5 shuffled, averaged, EMA applied", flush=True)
 
-    # whole population: every coordinate still holds the same multiset fingerprints
-    gx, gs = fold(pop)
-    assert torch.equal(gx, fx) and torch.equal(gs, fs)
-    gx, gs = fold(mom)
-    assert torch.equal(gx, mx) and torch.equal(gs, ms)
-    del fx, fs, mx, ms, gx, gs
+    W = 1 << 20
 
-    # selected count: binomial band around steps * sum_s p_s * len_s
+    def check(g0, blk, avg_chunk):
+        """blk: host [5, N, w] = initial params, initial momentum, final params, final momentum, EMA."""
+        w = blk.shape[2]
+        ref, refm = blk[0], blk[1]
+        local = [sg for sg in segs_list if sg[0] < g0 + w and sg[0] + sg[1] > g0]
+        c = 0
+        for step in range(steps):
+            c += oracle.shuffle_window(ref, refm, P, g0, local, cfg.seed, step, stream=stream)
+        assert np.array_equal(_bits(blk[2]), _bits(ref)), f"params differ in the chunk at {g0}"
+        assert np.array_equal(_bits(blk[3]), _bits(refm)), f"momentum differs in the chunk at {g0}"
+        abs_mean = np.abs(ref).mean(axis=0)
+        assert _close(avg_chunk, oracle.average(ref), abs_mean), f"average outside 1e-6 in the chunk at {g0}"
+        oracle.ema(ref, alpha)
+        assert _close(blk[4], ref, abs_mean[None, :]), f"EMA outside 1e-6 in the chunk at {g0}"
+        return c
+
+    ref_cnt, pending, done = 0, [], 0
+    with ThreadPoolExecutor(max_workers=THREADS) as pool:
+        for g0 in range(0, P, W):
+            g1 = min(P, g0 + W)
+            blk = torch.stack([t[:, g0:g1] for t in (pop0, mom0, pop, mom, ema)]).cpu().numpy()
+            pending.append(pool.submit(check, g0, blk, avg[g0:g1].cpu().numpy()))
+            while len(pending) > 2 * THREADS:
+                ref_cnt += pending.pop(0).result()
+                done += 1
+                if done % 128 == 0:
+                    print(f"config 5: {done} chunks compared", flush=True)
+        for f in pending:
+            ref_cnt += f.result()
+    assert int(cnt.item()) == ref_cnt and ref_cnt > 0
+    # Table 1's volume: the count is what Sec. 3 calls the communication per model, sum_s p_s * len_s per step
     mean = steps * sum(length * p for _, length, p in segs_list)
     var = steps * sum(length * p * (1 - p) for _, length, p in segs_list)
-    assert abs(int(cnt.item()) - mean) < 6 * math.sqrt(var)
+    assert abs(ref_cnt - mean) < 6 * math.sqrt(var)
 
-    avg = wash.wash_average(pop)
-    for g0, w, (ip, im) in zip(starts, widths, init):
-        print(f"config 5 window at {g0} width {w}", flush=True)
-        ref, refm = ip.cpu().numpy(), im.cpu().numpy()
-        for step in range(steps):
-            oracle.shuffle_window(ref, refm, P, g0, segs_list, cfg.seed, step, stream=stream)
-        got = pop[:, g0:g0 + w].contiguous().cpu().numpy()
-        gotm = mom[:, g0:g0 + w].contiguous().cpu().numpy()
-        assert np.array_equal(_bits(got), _bits(ref)), f"params window {g0}"
-        assert np.array_equal(_bits(gotm), _bits(refm)), f"momentum window {g0}"
-        assert not np.array_equal(_bits(got), _bits(ip.cpu().numpy()))
-        ref_avg = oracle.average(ref)
-        assert _close(avg[g0:g0 + w].cpu().numpy(), ref_avg, np.abs(ref).mean(axis=0)), f"average window {g0}"
+
+@pytest.mark.parametrize("nbuf", [3, 4])
+def test_dense_path_beyond_4gib_with_several_states(wash, nbuf):
+    """WASH+Opt with 3 and 4 buffers at p = 0.1 on more than 4 GiB: the streaming (dense) kernel with
+    non-temporal accesses, which smaller cases never reach.  Every buffer must end up as the oracle
+    leaves it when it shuffles that buffer alone with the same (seed, step)."""
+    N, P = 8, 46_000_003
+    assert N * P * 4 * nbuf >= 4 << 30
+    segs_list = [(0, P // 3, 0.1), (P // 3, P - P // 3 - 5, 0.25), (P - 5, 5, 1.0)]
+    gen = torch.Generator(device="cuda").manual_seed(41 + nbuf)
+    bufs = [torch.randn(N, P, device="cuda", generator=gen) * (0.02 if k == 0 else 1e-3) for k in range(nbuf)]
+    hosts = [b.cpu().numpy() for b in bufs]
+    cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+    print(f"dense path, {nbuf} buffers, {N * P * 4 * nbuf / 2**30:.1f} GiB", flush=True)
+    wash.wash_shuffle_states(bufs, segs_list, 17, 3, gap_stream=False, selected_count=cnt)
+    torch.cuda.synchronize()
+    for k, (b, h) in enumerate(zip(bufs, hosts)):
+        ref_cnt = oracle.shuffle(h, None, segs_list, 17, 3, threads=THREADS)
+        assert int(cnt.item()) == ref_cnt
+        assert np.array_equal(_bits(b.cpu().numpy()), _bits(h)), f"buffer {k} differs from the oracle"
 
 
 @pytest.mark.parametrize("stream", STREAMS)
