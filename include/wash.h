@@ -286,13 +286,14 @@ const char *wash_last_error_detail(void);
  * on them).  Returns WASH_EINVAL for an unknown option or a value out of range.
  *   WASH_OPT_TILE_COORDS  coordinates scanned by one wavefront in wash_shuffle;
  *                         a multiple of 256 in [256, 65536], or 0 = choose by P, N and the probabilities
- *   WASH_OPT_STREAM_MIN_BYTES  papa_ema uses non-temporal (cache-bypassing) accesses when the
- *                         population N*P*4 is at least this many bytes (default 256 MiB;
- *                         smaller populations are left to the 256 MB Infinity Cache)
+ *   WASH_OPT_STREAM_MIN_BYTES  from this population size N*P*4 on (default 256 MiB, the size of the
+ *                         Infinity Cache) papa_ema and wash_average run in their streaming shape:
+ *                         non-temporal accesses and a capped number of blocks per compute unit
  *   WASH_OPT_GAP_BLOCKS   1024-coordinate blocks walked by one wavefront in wash_shuffle_gap;
  *                         a power of two in [1, 64], or 0 = choose by P and p
- *   WASH_OPT_AVERAGE_CHUNKS  1024-coordinate chunks owned by one block of wash_average: 1, 2, 4, 8,
- *                         or 0 = choose by N and P (8 when many long rows are read, else 1 or 4)
+ *   WASH_OPT_AVERAGE_CHUNKS  0 = wash_average chooses its kernel and launch shape from N and P;
+ *                         1, 2, 4, 8 = force the kernel that reads the rows one after the other,
+ *                         with that many 1024-coordinate chunks per block
  *   WASH_OPT_DENSE        wash_shuffle has a second code path that streams whole rows through
  *                         on-chip memory instead of gathering single values (same results);
  *                         0 = use it inside segments whose probability is high enough for it

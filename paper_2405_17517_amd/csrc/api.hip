@@ -447,8 +447,9 @@ int wash_average(const float *params, float *out, uint32_t N, uint64_t P, void *
     if (out == nullptr) return fail(WASH_EINVAL, "out is NULL");
     if (ranges_overlap(params, static_cast<uint64_t>(N) * P * sizeof(float), out, P * sizeof(float)))
         return fail(WASH_EINVAL, "out overlaps params");
-    const int chunks = g_average_chunks != 0 ? static_cast<int>(g_average_chunks) : wash::average_chunks_for(N, P);
-    const hipError_t e = wash::launch_average(params, out, N, P, chunks, static_cast<hipStream_t>(stream));
+    const int chunks = static_cast<int>(g_average_chunks);     // 0: the launcher chooses kernel and shape
+    const bool streaming = static_cast<int64_t>(N * P * sizeof(float)) >= g_stream_min_bytes;
+    const hipError_t e = wash::launch_average(params, out, N, P, chunks, streaming, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail_hip("wash_average launch", e);
     return WASH_OK;
 }

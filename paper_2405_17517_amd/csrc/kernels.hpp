@@ -51,8 +51,10 @@ hipError_t launch_shuffle_gap(const ShuffleArgs &a, hipStream_t stream);
 size_t shuffle_dense_lds_bytes(uint32_t N, uint32_t nbufs);
 hipError_t launch_shuffle_dense(const ShuffleArgs &a, hipStream_t stream, bool finish = true);
 hipError_t launch_step_advance(unsigned long long *step_advance, hipStream_t stream);   // *step_advance += 1
+// chunks_per_block: 0 = choose kernel and launch shape from N and P; 1, 2, 4, 8 = the row-after-row kernel with
+// that many 1024-coordinate chunks per block.  streaming: the population does not fit the Infinity Cache.
 hipError_t launch_average(const float *params, float *out, uint32_t N, uint64_t P, int chunks_per_block,
-                          hipStream_t stream);
+                          bool streaming, hipStream_t stream);
 // weights of wash_weighted_average, passed by value as a kernel argument
 struct Weights {
     double w[32];

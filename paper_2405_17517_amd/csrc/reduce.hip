@@ -8,7 +8,25 @@
 // and writes each element exactly once.  Rows are P elements apart and P need not be a multiple
 // of 4, so the 16-byte accesses are only 4-byte aligned; gfx950 global memory
 // accepts that.
+//
+// Launch shape in the streaming regime (population beyond the 256 MB Infinity Cache).  What these
+// kernels are up against is not latency but DRAM page locality: all blocks in flight read (and write)
+// a window of every row at once, and the wider that window, the more DRAM pages are open at a time
+// and the more often a page is closed before its neighbours' requests arrive.  Measured on MI355X,
+// N = 8, P = 1.1e9: the EMA reaches 68 % of 8 TB/s at full occupancy (32 wavefronts per compute
+// unit), 74 % at 8-12, 79 % at 5, 55 % at 2-3; the best point sits where about 40 KB (EMA) to 60 KB
+// (average) of loads are in flight per compute unit, whatever N is.  Occupancy is therefore capped on
+// purpose, by asking for dynamic LDS the kernel never touches (160 KB per compute unit: a block that
+// asks for 160/k KB leaves room for k blocks).  The hardware dispatcher hands out blocks in order
+// as others retire, which keeps the window compact; persistent grid-stride variants let it spread
+// (fast wavefronts run ahead) and measured 55-65 %.
+// Rows whose byte pitch is not a multiple of 128 cost 6-10 points: the first and last cache line of
+// every per-row piece is then shared with another block, read twice and written in two partial
+// pieces.  Blocks of 256 threads (4 KB per row) have a quarter of the seams of single wavefronts
+// (1 KB per row), so they are used there; aligned rows do best with single-wavefront blocks.
 #include "kernels.hpp"
+
+#include <atomic>
 
 namespace wash {
 
@@ -92,10 +110,47 @@ __global__ __launch_bounds__(kThreads) void average_kernel(const float *__restri
     }
 }
 
-template <int N, bool NT>
-__global__ __launch_bounds__(kThreads) void ema_kernel(float *__restrict__ params, uint64_t P, double alpha)
+// The average with all N loads of a thread in flight at once (N a template parameter), for the
+// streaming regime with N >= 5: same sums in the same order, launched with capped occupancy.
+template <int N, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void average_inflight_kernel(const float *__restrict__ params,
+                                                                 float *__restrict__ out, uint64_t P)
 {
-    const uint64_t base = (static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4u;
+    const uint64_t base = (static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x) * 4u;
+    if (base >= P) return;
+    const double den = static_cast<double>(N);
+    if (base + 4u <= P) {
+        f4u v[N];
+#pragma unroll
+        for (int n = 0; n < N; ++n) v[n] = load4<true>(params + static_cast<uint64_t>(n) * P + base);
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+#pragma unroll
+        for (int n = 0; n < N; ++n) {
+            s0 += static_cast<double>(v[n].x);
+            s1 += static_cast<double>(v[n].y);
+            s2 += static_cast<double>(v[n].z);
+            s3 += static_cast<double>(v[n].w);
+        }
+        f4u o;
+        o.x = static_cast<float>(s0 / den);
+        o.y = static_cast<float>(s1 / den);
+        o.z = static_cast<float>(s2 / den);
+        o.w = static_cast<float>(s3 / den);
+        store4<true>(out + base, o);
+    } else {
+        for (uint64_t g = base; g < P; ++g) {
+            double t = 0.0;
+#pragma unroll
+            for (int n = 0; n < N; ++n) t += static_cast<double>(params[static_cast<uint64_t>(n) * P + g]);
+            out[g] = static_cast<float>(t / den);
+        }
+    }
+}
+
+template <int N, bool NT, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void ema_kernel(float *__restrict__ params, uint64_t P, double alpha)
+{
+    const uint64_t base = (static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x) * 4u;
     if (base >= P) return;
     const double den = static_cast<double>(N);
     const double beta = 1.0 - alpha;
@@ -151,22 +206,102 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const float *__restrict_
     }
 }
 
-inline bool grid_for(uint64_t P, dim3 &grid)
+inline bool grid_for(uint64_t P, int block, dim3 &grid)
 {
     const uint64_t threads = (P + 3u) / 4u;
-    const uint64_t blocks = (threads + kThreads - 1) / kThreads;
+    const uint64_t blocks = (threads + block - 1) / block;
     if (blocks == 0 || blocks > 0x7FFFFFFFull) return false;
     grid = dim3(static_cast<uint32_t>(blocks));
     return true;
+}
+
+// Dynamic LDS (never touched by the kernel) that lets exactly `blocks_per_cu` blocks share the 160 KB of a
+// compute unit; 0 = no cap.  Valid for 1 .. 20 blocks.
+constexpr uint32_t kLdsPerCu = 160u * 1024u;
+inline uint32_t occupancy_pad_bytes(int blocks_per_cu)
+{
+    if (blocks_per_cu <= 0 || blocks_per_cu > 20) return 0;
+    return (kLdsPerCu - 1024u) / static_cast<uint32_t>(blocks_per_cu) / 256u * 256u;
+}
+
+// More than 64 KB of dynamic LDS has to be allowed per kernel (once per device).
+constexpr int kMaxDevices = 64;
+template <auto Kernel>
+hipError_t allow_large_lds()
+{
+    static std::atomic<bool> done[kMaxDevices];
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    if (done[device].load(std::memory_order_acquire)) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            static_cast<int>(kLdsPerCu - 1024u));
+    if (e == hipSuccess) done[device].store(true, std::memory_order_release);
+    return e;
+}
+
+struct LaunchShape {
+    int block;           // threads per block: 64 or 256
+    int blocks_per_cu;   // occupancy cap, 0 = none
+};
+
+// Measured best shapes (MI355X; see the note at the top of this file).  `aligned`: the byte pitch of a row is a
+// multiple of 128.
+inline LaunchShape ema_shape(uint32_t N, bool aligned)
+{
+    const int waves = static_cast<int>((40u + N / 2u) / N);            // about 40 KB of loads in flight per compute unit
+    if (aligned || N <= 4) return LaunchShape{64, waves < 5 ? 5 : (waves > 17 ? 17 : waves)};
+    const int blocks = static_cast<int>((10u + N / 2u) / N);           // the same in blocks of four wavefronts
+    return LaunchShape{256, blocks < 1 ? 1 : blocks};
+}
+inline LaunchShape average_shape(uint32_t N, bool aligned)
+{
+    if (aligned) {
+        const int waves = static_cast<int>((60u + N / 2u) / N);        // about 60 KB in flight
+        return LaunchShape{64, waves < 5 ? 5 : (waves > 16 ? 16 : waves)};
+    }
+    const int blocks = static_cast<int>((16u + N / 2u) / N);
+    return LaunchShape{256, blocks < 1 ? 1 : (blocks > 4 ? 4 : blocks)};
 }
 
 template <int N>
 hipError_t run_ema(float *params, uint64_t P, double alpha, bool nt, hipStream_t stream)
 {
     dim3 grid;
-    if (!grid_for(P, grid)) return hipErrorInvalidConfiguration;
-    if (nt) hipLaunchKernelGGL((ema_kernel<N, true>), grid, dim3(kThreads), 0, stream, params, P, alpha);
-    else hipLaunchKernelGGL((ema_kernel<N, false>), grid, dim3(kThreads), 0, stream, params, P, alpha);
+    if (!nt) {
+        // population inside the Infinity Cache: plain accesses, full occupancy
+        if (!grid_for(P, kThreads, grid)) return hipErrorInvalidConfiguration;
+        hipLaunchKernelGGL((ema_kernel<N, false, kThreads>), grid, dim3(kThreads), 0, stream, params, P, alpha);
+        return hipGetLastError();
+    }
+    const LaunchShape shape = ema_shape(N, (P % 32u) == 0);
+    const uint32_t pad = occupancy_pad_bytes(shape.blocks_per_cu);
+    if (!grid_for(P, shape.block, grid)) return hipErrorInvalidConfiguration;
+    if (shape.block == 64) {
+        if (const hipError_t e = allow_large_lds<ema_kernel<N, true, 64>>()) return e;
+        hipLaunchKernelGGL((ema_kernel<N, true, 64>), grid, dim3(64), pad, stream, params, P, alpha);
+    } else {
+        if (const hipError_t e = allow_large_lds<ema_kernel<N, true, kThreads>>()) return e;
+        hipLaunchKernelGGL((ema_kernel<N, true, kThreads>), grid, dim3(kThreads), pad, stream, params, P, alpha);
+    }
+    return hipGetLastError();
+}
+
+template <int N>
+hipError_t run_average_inflight(const float *params, float *out, uint64_t P, hipStream_t stream)
+{
+    const LaunchShape shape = average_shape(N, (P % 32u) == 0);
+    const uint32_t pad = occupancy_pad_bytes(shape.blocks_per_cu);
+    dim3 grid;
+    if (!grid_for(P, shape.block, grid)) return hipErrorInvalidConfiguration;
+    if (shape.block == 64) {
+        if (const hipError_t e = allow_large_lds<average_inflight_kernel<N, 64>>()) return e;
+        hipLaunchKernelGGL((average_inflight_kernel<N, 64>), grid, dim3(64), pad, stream, params, out, P);
+    } else {
+        if (const hipError_t e = allow_large_lds<average_inflight_kernel<N, kThreads>>()) return e;
+        hipLaunchKernelGGL((average_inflight_kernel<N, kThreads>), grid, dim3(kThreads), pad, stream, params, out, P);
+    }
     return hipGetLastError();
 }
 
@@ -179,7 +314,7 @@ hipError_t run_ema(float *params, uint64_t P, double alpha, bool nt, hipStream_t
 hipError_t launch_copy(const float *src, float *dst, uint64_t n, hipStream_t stream)
 {
     dim3 grid;
-    if (!grid_for(n, grid)) return hipErrorInvalidConfiguration;
+    if (!grid_for(n, kThreads, grid)) return hipErrorInvalidConfiguration;
     hipLaunchKernelGGL(copy_kernel, grid, dim3(kThreads), 0, stream, src, dst, n);
     return hipGetLastError();
 }
@@ -194,9 +329,23 @@ hipError_t run_average(const float *params, float *out, uint32_t N, uint64_t P, 
     return hipGetLastError();
 }
 
-hipError_t launch_average(const float *params, float *out, uint32_t N, uint64_t P, int chunks, hipStream_t stream)
+hipError_t launch_average(const float *params, float *out, uint32_t N, uint64_t P, int chunks, bool streaming,
+                          hipStream_t stream)
 {
     if (N == 0) return hipErrorInvalidValue;
+    if (chunks == 0) {
+        // automatic: beyond the Infinity Cache and from five models on, all N loads in flight under an occupancy cap;
+        // otherwise the rows one after the other at full occupancy
+        if (N >= 5 && streaming) {
+            switch (N) {
+#define X(n) case n: return run_average_inflight<n>(params, out, P, stream);
+                WASH_FOR_EACH_N(X)
+#undef X
+            default: return hipErrorInvalidValue;
+            }
+        }
+        return run_average<1>(params, out, N, P, stream);
+    }
     switch (chunks) {
     case 8: return run_average<8>(params, out, N, P, stream);
     case 4: return run_average<4>(params, out, N, P, stream);

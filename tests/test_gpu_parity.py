@@ -174,6 +174,28 @@ def test_shuffle_is_deterministic_and_tile_independent(wash):
         assert np.array_equal(_bits(o), _bits(outs[0]))
 
 
+@pytest.mark.parametrize("N", range(1, 33))
+def test_average_and_ema_streaming_shapes_every_population_size(wash, N):
+    """The launch shapes used beyond the Infinity Cache (occupancy-capped blocks of 64 or 256 threads, all N
+    loads in flight), forced on small inputs through the size threshold: every population size (each is its
+    own kernel instantiation), rows whose pitch is a multiple of 128 bytes and rows whose pitch is not, a
+    ragged last vector; average (Alg. 1 output) and EMA (Eq. 1) bit-identical to the oracle."""
+    wash.wash_set_option(wash.OPT_STREAM_MIN_BYTES, 0)
+    try:
+        for P in (32 * 2049, 70_001 + N, 259):
+            print(f"streaming shapes N={N} P={P}", flush=True)
+            rng = np.random.default_rng(N * 131 + P)
+            pop = (rng.standard_normal((N, P)) * 0.02).astype(np.float32)
+            d = torch.from_numpy(pop).cuda()
+            assert np.array_equal(wash.wash_average(d).cpu().numpy(), oracle.average(pop)), (N, P)
+            wash.papa_ema(d, 0.99)
+            ref = pop.copy()
+            oracle.ema(ref, 0.99)
+            assert np.array_equal(d.cpu().numpy(), ref), (N, P)
+    finally:
+        wash.wash_set_option(wash.OPT_STREAM_MIN_BYTES, 256 << 20)
+
+
 @pytest.mark.parametrize("N,P", [(1, 5), (2, 1023), (4, 1 << 20), (5, 1000003), (10, 300001), (20, 70002), (32, 4099)])
 def test_average_and_ema(wash, N, P):
     print(f"case N={N} P={P}", flush=True)
