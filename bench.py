@@ -429,6 +429,8 @@ def main():
     ap.add_argument("--gap-blocks", type=int, default=None, help="override blocks per wavefront of the gap kernel")
     ap.add_argument("--average-chunks", type=int, default=None, help="chunks per block of wash_average (1, 2, 4, 8)")
     ap.add_argument("--tile-coords", type=int, default=None, help="override the shuffle tile size")
+    ap.add_argument("--shuffle-blocks-per-cu", type=int, default=None,
+                    help="cap on resident blocks per compute unit of the gathering shuffle kernel (0 = none)")
     ap.add_argument("--dense", type=int, default=None, choices=[0, 1, 2],
                     help="wash_shuffle's dense path: 0 automatic, 1 never, 2 whenever it fits")
     ap.add_argument("--only", choices=["pass", "copy"], default="pass",
@@ -459,6 +461,8 @@ def main():
         wash.wash_set_option(wash.OPT_TILE_COORDS, args.tile_coords)
     if args.dense is not None:
         wash.wash_set_option(wash.OPT_DENSE, args.dense)
+    if args.shuffle_blocks_per_cu is not None:
+        wash.wash_set_option(wash.OPT_SHUFFLE_BLOCKS_PER_CU, args.shuffle_blocks_per_cu)
 
     if args.only == "copy":
         print(json.dumps({"copy_yardstick": copy_yardstick(torch, wash)}))

@@ -294,6 +294,8 @@ const char *wash_last_error_detail(void);
  *   WASH_OPT_AVERAGE_CHUNKS  0 = wash_average chooses its kernel and launch shape from N and P;
  *                         1, 2, 4, 8 = force the kernel that reads the rows one after the other,
  *                         with that many 1024-coordinate chunks per block
+ *   WASH_OPT_SHUFFLE_BLOCKS_PER_CU  cap on the blocks (of four wavefronts) of the gathering shuffle
+ *                         kernel resident on one compute unit: 1 .. 20, or 0 = no cap
  *   WASH_OPT_DENSE        wash_shuffle has a second code path that streams whole rows through
  *                         on-chip memory instead of gathering single values (same results);
  *                         0 = use it inside segments whose probability is high enough for it
@@ -304,6 +306,7 @@ const char *wash_last_error_detail(void);
 #define WASH_OPT_GAP_BLOCKS 3
 #define WASH_OPT_STREAM_MIN_BYTES 2
 #define WASH_OPT_DENSE 5
+#define WASH_OPT_SHUFFLE_BLOCKS_PER_CU 6
 int wash_set_option(int option, int64_t value);
 
 /* Free the cached device tables of every device (waits for the devices). */

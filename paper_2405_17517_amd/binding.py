@@ -19,6 +19,7 @@ OPT_STREAM_MIN_BYTES = 2
 OPT_GAP_BLOCKS = 3
 OPT_AVERAGE_CHUNKS = 4
 OPT_DENSE = 5
+OPT_SHUFFLE_BLOCKS_PER_CU = 6
 
 
 class WashError(RuntimeError):

@@ -60,8 +60,9 @@ struct TableKey {
 
 struct Table {
     TableKey key;
-    void *dev = nullptr;            // [count slots][DevSegment x nsegs][uint32 x num_tiles]
+    void *dev = nullptr;            // [uint32 x kCountSlots: active tiles per ticket word][DevSegment x nsegs][uint32 x num_tiles]
     uint64_t num_tiles = 0;
+    uint32_t active_words = 0;      // ticket words that at least one active tile reports to
     bool pinned = false;            // recorded into a captured graph: kept until wash_shutdown
 };
 
@@ -72,6 +73,7 @@ int64_t g_tile_coords_option = 0;   // 0 = choose by P
 int64_t g_gap_blocks_option = 0;    // 0 = choose by P
 int64_t g_average_chunks = 0;       // 1024-coordinate chunks per block of wash_average; 0 = choose by P
 int64_t g_dense_option = 0;         // wash_shuffle's dense path: 0 = by probability, 1 = never, 2 = whenever it fits
+int64_t g_shuffle_blocks_per_cu = 0; // cap on resident blocks per compute unit of the sparse shuffle kernel; 0 = none
 int64_t g_stream_min_bytes = 256ll << 20;  // papa_ema on populations at least this large uses non-temporal accesses
 
 // Coordinates scanned by one wavefront of wash_shuffle.  `moved_per_coord` is the expected number
@@ -109,23 +111,28 @@ int get_table(int device, uint64_t P, uint32_t tile_coords, bool gap, std::vecto
     const uint64_t num_tiles = (P + tile_coords - 1) / tile_coords;
     const size_t nsegs = key.segs.size();
     const size_t seg_bytes = nsegs * sizeof(wash::DevSegment);
-    const size_t bytes = wash::kCountSlotBytes + seg_bytes + num_tiles * sizeof(uint32_t);
+    const size_t bytes = wash::kExpectedBytes + seg_bytes + num_tiles * sizeof(uint32_t);
     std::vector<unsigned char> host;
     try {
         host.resize(bytes);
     } catch (const std::bad_alloc &) {
         return fail(WASH_ENOMEM, "segment table of %zu bytes", bytes);
     }
-    std::memset(host.data(), 0, wash::kCountSlotBytes);
-    std::memcpy(host.data() + wash::kCountSlotBytes, key.segs.data(), seg_bytes);
-    uint32_t *tile_first = reinterpret_cast<uint32_t *>(host.data() + wash::kCountSlotBytes + seg_bytes);
+    std::memset(host.data(), 0, wash::kExpectedBytes);
+    std::memcpy(host.data() + wash::kExpectedBytes, key.segs.data(), seg_bytes);
+    uint32_t *expected = reinterpret_cast<uint32_t *>(host.data());
+    uint32_t *tile_first = reinterpret_cast<uint32_t *>(host.data() + wash::kExpectedBytes + seg_bytes);
     size_t s = 0;
     for (uint64_t t = 0; t < num_tiles; ++t) {
         const uint64_t begin = t * tile_coords;
         const uint64_t end = (begin + tile_coords < P) ? begin + tile_coords : P;
         while (s < nsegs && key.segs[s].end <= begin) ++s;
-        tile_first[t] = (s < nsegs && key.segs[s].begin < end) ? static_cast<uint32_t>(s) : wash::kNoSegment;
+        const bool active = s < nsegs && key.segs[s].begin < end;
+        tile_first[t] = active ? static_cast<uint32_t>(s) : wash::kNoSegment;
+        if (active) ++expected[t % wash::kCountSlots];      // the tile's wavefront reports to this ticket word
     }
+    uint32_t active_words = 0;
+    for (uint32_t w = 0; w < wash::kCountSlots; ++w) active_words += expected[w] != 0 ? 1u : 0u;
     if (g_tables.size() >= kMaxTables) {
         // drop the least recently used table that no captured graph refers to (if every table is
         // pinned the cache grows); hipFree waits for the device, so no launched kernel still reads it
@@ -151,34 +158,108 @@ int get_table(int device, uint64_t P, uint32_t tile_coords, bool gap, std::vecto
     g_tables.front().key = std::move(key);
     g_tables.front().dev = dev;
     g_tables.front().num_tiles = num_tiles;
+    g_tables.front().active_words = active_words;
     *out = &g_tables.front();
     return WASH_OK;
 }
 
-// One scratch buffer per device for the partial sums of wash_consensus_sqdist (1 MiB, kept until shutdown).
-struct Scratch {
+// ---- workspaces: device memory a call needs beyond its arguments -----------------------------------------------
+// [ticket words of the shuffle kernels][partial sums of wash_consensus_sqdist], one per (device, stream), so that
+// calls on different streams never share any; calls on one stream are ordered.  A stream under capture gets a
+// workspace of its own per capture (the recorded kernels keep using it at every replay).  Nothing may be allocated
+// while a stream captures, so every allocation also sets a few spare workspaces aside for later captures.
+// Workspaces live until wash_shutdown.
+struct Workspace {
     int device;
+    bool assigned;                  // false: spare
+    bool capture;                   // key is a capture id, not a stream
+    unsigned long long key;
     void *dev;
 };
-std::vector<Scratch> g_scratch;
+std::vector<Workspace> g_workspaces;
+constexpr size_t kWorkspaceBytes = wash::kTicketBytes + wash::kSqdistScratchBytes;
+constexpr int kSpareWorkspaces = 3;
+constexpr size_t kMaxWorkspaces = 256;
 
-int get_scratch(int device, double **out)
+int new_workspace(int device, Workspace **out)
 {
-    for (const Scratch &sc : g_scratch)
-        if (sc.device == device) {
-            *out = static_cast<double *>(sc.dev);
-            return WASH_OK;
-        }
     void *dev = nullptr;
-    const hipError_t e = hipMalloc(&dev, wash::kSqdistScratchBytes);
-    if (e != hipSuccess) return fail_hip("hipMalloc(scratch)", e);
+    hipError_t e = hipMalloc(&dev, kWorkspaceBytes);
+    if (e != hipSuccess) return fail_hip("hipMalloc(workspace)", e);
+    e = hipMemset(dev, 0, wash::kTicketBytes);                  // ticket words are zero between calls
+    if (e != hipSuccess) {
+        (void)hipFree(dev);
+        return fail_hip("hipMemset(workspace)", e);
+    }
     try {
-        g_scratch.push_back(Scratch{device, dev});
+        g_workspaces.push_back(Workspace{device, false, false, 0, dev});
     } catch (const std::bad_alloc &) {
         (void)hipFree(dev);
-        return fail(WASH_ENOMEM, "scratch list");
+        return fail(WASH_ENOMEM, "workspace list");
     }
-    *out = static_cast<double *>(dev);
+    *out = &g_workspaces.back();
+    return WASH_OK;
+}
+
+// The workspace of `stream` on `device` (g_mutex held).  need = false: the call itself uses none, but, like every
+// call outside a capture, it makes sure that spares exist for captures to come.
+int get_workspace(int device, hipStream_t stream, bool need, void **out)
+{
+    *out = nullptr;
+    bool capturing = false;
+    unsigned long long key = reinterpret_cast<uintptr_t>(stream);
+    if (stream != nullptr) {
+        hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+        unsigned long long id = 0;
+        if (hipStreamGetCaptureInfo(stream, &status, &id) != hipSuccess) {
+            (void)hipGetLastError();
+        } else if (status == hipStreamCaptureStatusActive) {
+            capturing = true;
+            key = id;
+        }
+    }
+    void *mine = nullptr;
+    size_t spare_index = g_workspaces.size();
+    int spares = 0;
+    for (size_t k = 0; k < g_workspaces.size(); ++k) {
+        Workspace &w = g_workspaces[k];
+        if (w.device != device) continue;
+        if (w.assigned && w.capture == capturing && w.key == key) mine = w.dev;
+        if (!w.assigned) {
+            spare_index = k;
+            ++spares;
+        }
+    }
+    if (need && mine == nullptr) {
+        if (spare_index == g_workspaces.size()) {
+            if (capturing)
+                return fail(WASH_EHIP, "no workspace is set aside for this capture (device memory cannot be allocated while "
+                                       "a stream captures): make one call of the library on this device outside the capture first");
+            if (g_workspaces.size() >= kMaxWorkspaces)
+                return fail(WASH_ENOMEM, "more than %zu streams and captures have used the library", kMaxWorkspaces);
+            Workspace *fresh = nullptr;
+            if (int rc = new_workspace(device, &fresh)) return rc;
+            spare_index = g_workspaces.size() - 1;
+            ++spares;
+        }
+        Workspace &w = g_workspaces[spare_index];
+        w.assigned = true;
+        w.capture = capturing;
+        w.key = key;
+        mine = w.dev;
+        --spares;
+    }
+    if (!capturing) {
+        // keep a few spares for captures to come (failing to is not an error of this call)
+        for (; spares < kSpareWorkspaces && g_workspaces.size() < kMaxWorkspaces; ++spares) {
+            Workspace *extra = nullptr;
+            if (new_workspace(device, &extra) != WASH_OK) {
+                g_detail[0] = 0;
+                break;
+            }
+        }
+    }
+    *out = mine;
     return WASH_OK;
 }
 
@@ -306,6 +387,10 @@ static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t
         else
             capturing = capture == hipStreamCaptureStatusActive;
     }
+    // the selected count and the step advance are carried by ticket words in the workspace of this stream
+    void *workspace = nullptr;
+    if (int rc = get_workspace(device, hstream, selected_count != nullptr || (step_dev != nullptr && advance), &workspace))
+        return rc;
     // Finds or builds the device table of `list` and fills the kernel arguments that go with it.
     auto prepare = [&](std::vector<wash::DevSegment> &&list, uint32_t tile_coords, wash::ShuffleArgs *a) -> int {
         Table *table = nullptr;
@@ -318,19 +403,23 @@ static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t
         a->N = N;
         a->P = P;
         unsigned char *base = static_cast<unsigned char *>(table->dev);
-        a->segs = reinterpret_cast<const wash::DevSegment *>(base + wash::kCountSlotBytes);
+        a->segs = reinterpret_cast<const wash::DevSegment *>(base + wash::kExpectedBytes);
         a->nsegs = static_cast<uint32_t>(table->key.segs.size());
-        a->tile_first = reinterpret_cast<const uint32_t *>(base + wash::kCountSlotBytes +
+        a->tile_first = reinterpret_cast<const uint32_t *>(base + wash::kExpectedBytes +
                                                            table->key.segs.size() * sizeof(wash::DevSegment));
         a->num_tiles = table->num_tiles;
         a->tile_coords = tile_coords;
+        a->blocks_per_cu = static_cast<uint32_t>(g_shuffle_blocks_per_cu);
+        a->stream_stores = pop_bytes * nbufs >= (4ull << 30) ? 1u : 0u;
         a->key_lo = static_cast<uint32_t>(seed);
         a->key_hi = static_cast<uint32_t>(seed >> 32);
         a->step = static_cast<uint32_t>(step);
         a->step_ptr = reinterpret_cast<const unsigned long long *>(step_dev);
         a->step_advance = (step_dev != nullptr && advance) ? reinterpret_cast<unsigned long long *>(step_dev) : nullptr;
         a->selected_count = reinterpret_cast<unsigned long long *>(selected_count);
-        a->count_slots = selected_count ? reinterpret_cast<unsigned long long *>(base) : nullptr;
+        a->tickets = static_cast<unsigned long long *>(workspace);            // nullptr: no count, no step advance
+        a->expected = reinterpret_cast<const uint32_t *>(base);
+        a->active_words = table->active_words;
         return WASH_OK;
     };
 
@@ -346,6 +435,9 @@ static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t
         while (bpw > 1 && a.num_tiles / bpw < 2048) bpw >>= 1;
         if (g_gap_blocks_option != 0) bpw = static_cast<uint32_t>(g_gap_blocks_option);
         a.blocks_per_wave = bpw;
+        a.nwaves = (a.num_tiles + bpw - 1) / bpw;          // every wavefront of the grid reports
+        a.expected = nullptr;
+        a.active_words = static_cast<uint32_t>(a.nwaves < wash::kCountSlots ? a.nwaves : wash::kCountSlots);
         e = wash::launch_shuffle_gap(a, hstream);
         if (e != hipSuccess) return fail_hip("shuffle launch", e);
         return WASH_OK;
@@ -392,12 +484,12 @@ static int shuffle_common(bool gap, float *const *bufs, uint32_t nbufs, uint32_t
                              choose_tile_coords(P, expected_sparse / static_cast<double>(P) * N * nbufs), &as))
             return rc;
     if (have_dense) {
-        if (have_sparse) ad.count_slots = as.count_slots;     // one set of partial counters, folded once
+        if (have_sparse) ad.step_advance = nullptr;           // the step advances after the last kernel of the call
         ad.dense_nontemporal = pop_bytes * nbufs >= (4ull << 30) ? 1u : 0u;
-        e = wash::launch_shuffle_dense(ad, hstream, /*finish=*/!have_sparse);
+        e = wash::launch_shuffle_dense(ad, hstream);
         if (e != hipSuccess) return fail_hip("shuffle launch", e);
     }
-    if (have_sparse) e = wash::launch_shuffle(as, hstream, /*finish=*/true);
+    if (have_sparse) e = wash::launch_shuffle(as, hstream);
     if (e != hipSuccess) return fail_hip("shuffle launch", e);
     return WASH_OK;
 }
@@ -478,8 +570,9 @@ int wash_consensus_sqdist(const float *params, uint32_t N, uint64_t P, uint64_t 
     hipError_t e = hipGetDevice(&device);
     if (e != hipSuccess) return fail_hip("hipGetDevice", e);
     std::lock_guard<std::mutex> lock(g_mutex);
-    double *partial = nullptr;
-    if (int rc = get_scratch(device, &partial)) return rc;
+    void *workspace = nullptr;
+    if (int rc = get_workspace(device, static_cast<hipStream_t>(stream), true, &workspace)) return rc;
+    double *partial = reinterpret_cast<double *>(static_cast<unsigned char *>(workspace) + wash::kTicketBytes);
     e = wash::launch_sqdist(params, N, P, g_begin, g_end, partial, out, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail_hip("wash_consensus_sqdist launch", e);
     return WASH_OK;
@@ -615,6 +708,12 @@ int wash_set_option(int option, int64_t value)
         g_dense_option = value;
         return WASH_OK;
     }
+    if (option == WASH_OPT_SHUFFLE_BLOCKS_PER_CU) {
+        if (value < 0 || value > 20) return fail(WASH_EINVAL, "blocks per compute unit must be 0 (no cap) or 1 .. 20");
+        std::lock_guard<std::mutex> lock(g_mutex);
+        g_shuffle_blocks_per_cu = value;
+        return WASH_OK;
+    }
     if (option == WASH_OPT_STREAM_MIN_BYTES) {
         if (value < 0) return fail(WASH_EINVAL, "byte threshold must be >= 0");
         std::lock_guard<std::mutex> lock(g_mutex);
@@ -635,10 +734,10 @@ int wash_shutdown(void)
         if (hipSetDevice(t.key.device) != hipSuccess || hipFree(t.dev) != hipSuccess) rc = WASH_EHIP;
     }
     g_tables.clear();
-    for (Scratch &sc : g_scratch) {
-        if (hipSetDevice(sc.device) != hipSuccess || hipFree(sc.dev) != hipSuccess) rc = WASH_EHIP;
+    for (Workspace &w : g_workspaces) {
+        if (hipSetDevice(w.device) != hipSuccess || hipFree(w.dev) != hipSuccess) rc = WASH_EHIP;
     }
-    g_scratch.clear();
+    g_workspaces.clear();
     if (have_current) (void)hipSetDevice(current);
     return rc;
 }

@@ -30,26 +30,35 @@ struct ShuffleArgs {
                                 // gap stream: 1024 (a tile is one restart block; a wavefront walks `blocks_per_wave` of them)
     uint32_t blocks_per_wave;   // gap stream only: 1 .. 64
     uint32_t dense_nontemporal; // dense path only, read by the launcher: stream the rows past the caches
+    uint32_t stream_stores;     // gathering kernels, read by the launchers: scattered stores are non-temporal
+    uint32_t blocks_per_cu;     // read by the launchers: cap on resident blocks per compute unit (0 = none)
     uint32_t key_lo, key_hi;    // seed
     uint32_t step;              // used when step_ptr is nullptr
     const unsigned long long *step_ptr; // device step counter read by the kernel (its low 32 bits), or nullptr
     unsigned long long *step_advance;   // if set, incremented by one after the shuffle (by the kernel that follows it)
     unsigned long long *selected_count; // caller's counter, or nullptr
-    unsigned long long *count_slots;    // kCountSlots partial counters, all zero between calls; nullptr iff no counter
+    // End-of-kernel bookkeeping (selected count, step advance) without a second launch: every active wavefront
+    // adds (1 << 40 | its count) to one of kCountSlots ticket words; the wavefront that completes a word carries
+    // the word's sum to the final word, and the one that completes that adds the total to the caller's counter
+    // and advances the device step.  Words are zero between calls.  nullptr iff nothing was asked for.
+    unsigned long long *tickets;        // kCountSlots + 1 words, one 128-byte line each (workspace of the calling stream)
+    const uint32_t *expected;           // per ticket word: wavefronts that will report to it (tile kernels: active
+                                        // tiles with index = word mod kCountSlots); nullptr: every wavefront of the gap grid
+    uint32_t active_words;              // ticket words with expected > 0
+    uint64_t nwaves;                    // gap stream: wavefronts of the grid that own at least one block
 };
 
-// Partial counters of the selected-coordinate statistic: one 128-byte line each.
 constexpr uint32_t kCountSlots = 256;
-constexpr uint32_t kCountSlotStride = 16;   // in 8-byte words
-constexpr size_t kCountSlotBytes = static_cast<size_t>(kCountSlots) * kCountSlotStride * 8;
+constexpr uint32_t kCountSlotStride = 16;   // in 8-byte words: one cache line per ticket word
+constexpr size_t kTicketBytes = static_cast<size_t>(kCountSlots + 1) * kCountSlotStride * 8;
+constexpr size_t kExpectedBytes = static_cast<size_t>(kCountSlots) * sizeof(uint32_t);
 
-// finish: fold the selected count and advance the device step after the kernel (false for all but the last
-// kernel of a call that launches several)
-hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream, bool finish = true);
+// a.step_advance is set only for the last kernel of a call that launches several
+hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream);
 hipError_t launch_shuffle_gap(const ShuffleArgs &a, hipStream_t stream);
 // dense variant of launch_shuffle (same results): tile_coords must be 256; needs shuffle_dense_lds_bytes <= 64 KiB
 size_t shuffle_dense_lds_bytes(uint32_t N, uint32_t nbufs);
-hipError_t launch_shuffle_dense(const ShuffleArgs &a, hipStream_t stream, bool finish = true);
+hipError_t launch_shuffle_dense(const ShuffleArgs &a, hipStream_t stream);
 hipError_t launch_step_advance(unsigned long long *step_advance, hipStream_t stream);   // *step_advance += 1
 // chunks_per_block: 0 = choose kernel and launch shape from N and P; 1, 2, 4, 8 = the row-after-row kernel with
 // that many 1024-coordinate chunks per block.  streaming: the population does not fit the Infinity Cache.

@@ -279,10 +279,12 @@ hipError_t run_ema(float *params, uint64_t P, double alpha, bool nt, hipStream_t
     const uint32_t pad = occupancy_pad_bytes(shape.blocks_per_cu);
     if (!grid_for(P, shape.block, grid)) return hipErrorInvalidConfiguration;
     if (shape.block == 64) {
-        if (const hipError_t e = allow_large_lds<ema_kernel<N, true, 64>>()) return e;
+        if (pad > 65536u)
+            if (const hipError_t e = allow_large_lds<ema_kernel<N, true, 64>>()) return e;
         hipLaunchKernelGGL((ema_kernel<N, true, 64>), grid, dim3(64), pad, stream, params, P, alpha);
     } else {
-        if (const hipError_t e = allow_large_lds<ema_kernel<N, true, kThreads>>()) return e;
+        if (pad > 65536u)
+            if (const hipError_t e = allow_large_lds<ema_kernel<N, true, kThreads>>()) return e;
         hipLaunchKernelGGL((ema_kernel<N, true, kThreads>), grid, dim3(kThreads), pad, stream, params, P, alpha);
     }
     return hipGetLastError();
@@ -296,10 +298,12 @@ hipError_t run_average_inflight(const float *params, float *out, uint64_t P, hip
     dim3 grid;
     if (!grid_for(P, shape.block, grid)) return hipErrorInvalidConfiguration;
     if (shape.block == 64) {
-        if (const hipError_t e = allow_large_lds<average_inflight_kernel<N, 64>>()) return e;
+        if (pad > 65536u)
+            if (const hipError_t e = allow_large_lds<average_inflight_kernel<N, 64>>()) return e;
         hipLaunchKernelGGL((average_inflight_kernel<N, 64>), grid, dim3(64), pad, stream, params, out, P);
     } else {
-        if (const hipError_t e = allow_large_lds<average_inflight_kernel<N, kThreads>>()) return e;
+        if (pad > 65536u)
+            if (const hipError_t e = allow_large_lds<average_inflight_kernel<N, kThreads>>()) return e;
         hipLaunchKernelGGL((average_inflight_kernel<N, kThreads>), grid, dim3(kThreads), pad, stream, params, out, P);
     }
     return hipGetLastError();

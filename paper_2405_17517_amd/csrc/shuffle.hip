@@ -57,6 +57,28 @@ __device__ __forceinline__ uint32_t step_of(const ShuffleArgs &a)
     return a.step_ptr != nullptr ? static_cast<uint32_t>(*a.step_ptr) : a.step;
 }
 
+// Called once by every wavefront that `expected` counts, at its end (lane 0 acts): see ShuffleArgs::tickets.
+__device__ __forceinline__ void report_wave(const ShuffleArgs &a, uint64_t index, uint32_t selected)
+{
+    if (a.tickets == nullptr || lane_id() != 0) return;
+    const uint32_t word = static_cast<uint32_t>(index % kCountSlots);
+    const uint64_t expected = a.expected != nullptr ? a.expected[word]
+                                                    : a.nwaves / kCountSlots + (word < a.nwaves % kCountSlots ? 1u : 0u);
+    constexpr unsigned long long kOne = 1ull << 40, kSum = kOne - 1;      // a word sums at most P / 256 < 2^40
+    unsigned long long *slot = a.tickets + word * kCountSlotStride;
+    const unsigned long long now = atomicAdd(slot, kOne | selected) + (kOne | selected);
+    if ((now >> 40) != expected) return;
+    *slot = 0;                                                           // nobody else comes to this word in this kernel
+    constexpr unsigned long long kOne2 = 1ull << 48, kSum2 = kOne2 - 1;   // the total is at most P <= 2^40
+    unsigned long long *last = a.tickets + kCountSlots * kCountSlotStride;
+    const unsigned long long mine = kOne2 | (now & kSum);
+    const unsigned long long all = atomicAdd(last, mine) + mine;
+    if ((all >> 48) != a.active_words) return;
+    *last = 0;
+    if (a.selected_count != nullptr && (all & kSum2) != 0) atomicAdd(a.selected_count, all & kSum2);
+    if (a.step_advance != nullptr) *a.step_advance += 1;                  // every wavefront has read the step by now
+}
+
 typedef __attribute__((address_space(1))) const void *global_cptr;
 typedef __attribute__((address_space(3))) void *lds_ptr;
 
@@ -109,7 +131,11 @@ __device__ __forceinline__ void draw_swap_partners(const ShuffleArgs &a, uint32_
 // Gather, permute and scatter up to 64 queued coordinates, one per lane.
 // kBufs buffers (the parameters, then the optimizer states) share the mask and the permutation;
 // buffer b uses the slab at slab + b * N * 64.
-template <int kBufs, typename QueueEntry>
+// kStream: the scattered stores are non-temporal.  Request sizes and HBM bytes stay what they are (measured:
+// 81 bytes fetched and 25 bytes written per moved value with any of sc0 / sc1 / nt on the gathers or the stores),
+// but on populations far beyond the caches the kernel gains 3 % (N = 8, P = 1.1e9, two buffers: 14.65 -> 14.16 ms;
+// no change at 2 GB).  Non-temporal gathers lose 35-45 % and are not used.
+template <int kBufs, bool kStream, typename QueueEntry>
 __device__ __forceinline__ void permute_batch(const ShuffleArgs &a, uint32_t step, uint64_t tile_begin,
                                               const QueueEntry *queue, uint32_t nbatch, uint32_t *slab)
 {
@@ -156,7 +182,10 @@ __device__ __forceinline__ void permute_batch(const ShuffleArgs &a, uint32_t ste
                 uint32_t *sl = slab + b * slab_words;
                 const uint32_t vi = sl[i * kWave + lane];
                 const uint32_t vj = sl[j * kWave + lane];
-                if (write_row) col[b][static_cast<uint64_t>(i) * P] = vj;
+                if (write_row) {
+                    if (kStream) __builtin_nontemporal_store(vj, &col[b][static_cast<uint64_t>(i) * P]);
+                    else col[b][static_cast<uint64_t>(i) * P] = vj;
+                }
                 sl[j * kWave + lane] = vi;
             }
             if (j != i) moved |= 1u << j;
@@ -165,7 +194,10 @@ __device__ __forceinline__ void permute_batch(const ShuffleArgs &a, uint32_t ste
     }
     if (moved & 1u) {
 #pragma unroll
-        for (int b = 0; b < kBufs; ++b) col[b][0] = slab[b * slab_words + lane];
+        for (int b = 0; b < kBufs; ++b) {
+            if (kStream) __builtin_nontemporal_store(slab[b * slab_words + lane], &col[b][0]);
+            else col[b][0] = slab[b * slab_words + lane];
+        }
     }
 }
 
@@ -198,7 +230,7 @@ __device__ __forceinline__ void select_quad(const ShuffleArgs &a, uint32_t step,
     }
 }
 
-template <int kBufs>
+template <int kBufs, bool kStream>
 __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const ShuffleArgs a)
 {
     extern __shared__ uint32_t lds[];
@@ -247,7 +279,7 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
         queued += __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3);
         while (queued >= kWave) {
             wave_lds_sync();
-            permute_batch<kBufs>(a, step, tile_begin, queue + (queued - kWave), kWave, slab);
+            permute_batch<kBufs, kStream>(a, step, tile_begin, queue + (queued - kWave), kWave, slab);
             queued -= kWave;
             selected += kWave;
             wave_lds_sync();
@@ -255,13 +287,12 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_kernel(const S
     }
     if (queued > 0) {
         wave_lds_sync();
-        permute_batch<kBufs>(a, step, tile_begin, queue, queued, slab);
+        permute_batch<kBufs, kStream>(a, step, tile_begin, queue, queued, slab);
         selected += queued;
     }
-    // One atomic per wavefront on a single address would serialise the whole grid at the
-    // memory side; spread them over kCountSlots cache lines and let a tiny kernel fold them.
-    if (a.count_slots != nullptr && selected != 0 && lane == 0)
-        atomicAdd(a.count_slots + (tile % kCountSlots) * kCountSlotStride, static_cast<unsigned long long>(selected));
+    // One atomic per wavefront on a single address would serialise the whole grid at the memory side
+    // (measured: 92 us instead of 14 on 2728 wavefronts); the reports are spread over kCountSlots cache lines.
+    report_wave(a, tile, selected);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -301,7 +332,10 @@ __global__ __launch_bounds__(kWave) void shuffle_dense_kernel(const ShuffleArgs 
     select_quad(a, step, (begin >> 2) + lane, end, uniform, seg0, walk, sel);
     const uint64_t b0 = __ballot(sel[0]), b1 = __ballot(sel[1]), b2 = __ballot(sel[2]), b3 = __ballot(sel[3]);
     const uint32_t count = __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3);
-    if (count == 0) return;
+    if (count == 0) {
+        report_wave(a, tile, 0);
+        return;
+    }
 
     // [selected offsets: 256 x u16][slab: kBufs x N rows x 256 coordinates]
     uint16_t *picked = reinterpret_cast<uint16_t *>(lds);
@@ -383,31 +417,13 @@ __global__ __launch_bounds__(kWave) void shuffle_dense_kernel(const ShuffleArgs 
             }
         }
     }
-    if (a.count_slots != nullptr && lane == 0)
-        atomicAdd(a.count_slots + (tile % kCountSlots) * kCountSlotStride, static_cast<unsigned long long>(count));
+    report_wave(a, tile, count);
 }
 
-// Runs after the shuffle kernel on the same stream.  Adds the per-slot partial counts to the caller's
-// counter and clears the slots for the next call (slots == nullptr: no count was asked for), and
-// advances the device step counter if there is one.
-__global__ __launch_bounds__(kCountSlots) void fold_count_kernel(unsigned long long *slots,
-                                                                 unsigned long long *selected_count,
-                                                                 unsigned long long *step_advance)
+// A call with nothing to shuffle still advances the device step counter.
+__global__ void step_advance_kernel(unsigned long long *step_advance)
 {
-    if (threadIdx.x == 0 && step_advance != nullptr) *step_advance += 1;
-    if (slots == nullptr) return;
-    __shared__ unsigned long long partial[kCountSlots / kWave];
-    unsigned long long v = slots[threadIdx.x * kCountSlotStride];
-    if (v != 0) slots[threadIdx.x * kCountSlotStride] = 0;
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_down(v, off, kWave);
-    if ((threadIdx.x % kWave) == 0) partial[threadIdx.x / kWave] = v;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        unsigned long long total = 0;
-        for (uint32_t w = 0; w < kCountSlots / kWave; ++w) total += partial[w];
-        if (total != 0) atomicAdd(selected_count, total);
-    }
+    if (threadIdx.x == 0 && blockIdx.x == 0) *step_advance += 1;
 }
 
 
@@ -422,7 +438,7 @@ __global__ __launch_bounds__(kCountSlots) void fold_count_kernel(unsigned long l
 
 constexpr uint32_t kGapQueueCap = 512;       // finds a wavefront can park between two flushes, shared by its lanes
 
-template <int kBufs>
+template <int kBufs, bool kStream>
 __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_gap_kernel(const ShuffleArgs a)
 {
     extern __shared__ uint32_t lds[];
@@ -512,38 +528,58 @@ __global__ __launch_bounds__(kWave * kWavesPerBlock) void shuffle_gap_kernel(con
         parked = 0;
         wave_lds_sync();
         for (uint32_t done = 0; done < total; done += kWave) {
-            permute_batch<kBufs>(a, step, tile_begin, queue + done, min(total - done, static_cast<uint32_t>(kWave)), slab);
+            permute_batch<kBufs, kStream>(a, step, tile_begin, queue + done, min(total - done, static_cast<uint32_t>(kWave)), slab);
         }
         selected += total;
         wave_lds_sync();
     }
-    if (a.count_slots != nullptr && selected != 0 && lane == 0)
-        atomicAdd(a.count_slots + (wave % kCountSlots) * kCountSlotStride, static_cast<unsigned long long>(selected));
+    report_wave(a, wave, selected);
 }
 
 }  // namespace
 
+// Dynamic LDS a block asks for beyond what it uses, so that at most `blocks_per_cu` blocks share the 160 KB of a
+// compute unit (0: no cap).  `used` is what the kernel itself needs.
+static size_t lds_with_cap(size_t used, uint32_t blocks_per_cu)
+{
+    if (blocks_per_cu == 0 || blocks_per_cu > 20) return used;
+    const size_t want = (160u * 1024u - 1024u) / blocks_per_cu / 256u * 256u;
+    return want > used ? want : used;
+}
+
+template <auto Kernel>
+static hipError_t allow_large_lds()
+{
+    static bool done[64] = {};
+    int device = 0;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    if (device < 0 || device >= 64) return hipErrorInvalidDevice;
+    if (done[device]) return hipSuccess;          // callers hold the library mutex
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            159 * 1024);
+    if (e == hipSuccess) done[device] = true;
+    return e;
+}
+
 hipError_t launch_step_advance(unsigned long long *step_advance, hipStream_t stream)
 {
-    hipLaunchKernelGGL(fold_count_kernel, dim3(1), dim3(kCountSlots), 0, stream,
-                       static_cast<unsigned long long *>(nullptr), static_cast<unsigned long long *>(nullptr), step_advance);
+    hipLaunchKernelGGL(step_advance_kernel, dim3(1), dim3(kWave), 0, stream, step_advance);
     return hipGetLastError();
 }
 
-// the kernel that follows the last shuffle kernel of a call
-static hipError_t finish_call(const ShuffleArgs &a, hipStream_t stream)
+// a kernel with nothing to do: only the step advance is left of the call
+static hipError_t nothing_to_launch(const ShuffleArgs &a, hipStream_t stream)
 {
-    if (a.count_slots == nullptr && a.step_advance == nullptr) return hipSuccess;
-    hipLaunchKernelGGL(fold_count_kernel, dim3(1), dim3(kCountSlots), 0, stream, a.count_slots, a.selected_count,
-                       a.step_advance);
-    return hipGetLastError();
+    return a.step_advance != nullptr ? launch_step_advance(a.step_advance, stream) : hipSuccess;
 }
 
-hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream, bool finish)
+hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream)
 {
-    if (a.num_tiles == 0 || a.nsegs == 0) return finish ? finish_call(a, stream) : hipSuccess;
+    if (a.num_tiles == 0 || a.nsegs == 0) return nothing_to_launch(a, stream);
     // the direct-to-LDS loads address LDS through a 16-bit offset: keep a block's partition below 64 KiB
     if (a.nbufs == 0 || a.nbufs > kMaxBufs) return hipErrorInvalidValue;
+    if (a.tickets != nullptr && a.expected == nullptr) return hipErrorInvalidValue;
     const size_t per_wave = (kQueueCap / 2 + static_cast<size_t>(a.N) * kWave * a.nbufs) * sizeof(uint32_t);
     uint32_t waves = kWavesPerBlock;
     while (waves > 1 && per_wave * waves > 65536) waves >>= 1;
@@ -551,16 +587,31 @@ hipError_t launch_shuffle(const ShuffleArgs &a, hipStream_t stream, bool finish)
     const uint64_t blocks64 = (a.num_tiles + waves - 1) / waves;
     if (blocks64 > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
     const dim3 grid(static_cast<uint32_t>(blocks64)), block(kWave * waves);
-    const size_t lds_bytes = per_wave * waves;
-    switch (a.nbufs) {
-    case 1: hipLaunchKernelGGL(shuffle_kernel<1>, grid, block, lds_bytes, stream, a); break;
-    case 2: hipLaunchKernelGGL(shuffle_kernel<2>, grid, block, lds_bytes, stream, a); break;
-    case 3: hipLaunchKernelGGL(shuffle_kernel<3>, grid, block, lds_bytes, stream, a); break;
-    default: hipLaunchKernelGGL(shuffle_kernel<4>, grid, block, lds_bytes, stream, a); break;
+    const size_t lds_bytes = lds_with_cap(per_wave * waves, a.blocks_per_cu);
+    hipError_t ea = hipSuccess;
+#define WASH_LAUNCH_SPARSE(B, S)                                                                                   \
+    do {                                                                                                           \
+        if (lds_bytes > 65536) ea = allow_large_lds<shuffle_kernel<B, S>>();                                       \
+        if (ea == hipSuccess) hipLaunchKernelGGL((shuffle_kernel<B, S>), grid, block, lds_bytes, stream, a);      \
+    } while (0)
+    if (a.stream_stores) {
+        switch (a.nbufs) {
+        case 1: WASH_LAUNCH_SPARSE(1, true); break;
+        case 2: WASH_LAUNCH_SPARSE(2, true); break;
+        case 3: WASH_LAUNCH_SPARSE(3, true); break;
+        default: WASH_LAUNCH_SPARSE(4, true); break;
+        }
+    } else {
+        switch (a.nbufs) {
+        case 1: WASH_LAUNCH_SPARSE(1, false); break;
+        case 2: WASH_LAUNCH_SPARSE(2, false); break;
+        case 3: WASH_LAUNCH_SPARSE(3, false); break;
+        default: WASH_LAUNCH_SPARSE(4, false); break;
+        }
     }
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess || !finish) return e;
-    return finish_call(a, stream);
+#undef WASH_LAUNCH_SPARSE
+    if (ea != hipSuccess) return ea;
+    return hipGetLastError();
 }
 
 size_t shuffle_dense_lds_bytes(uint32_t N, uint32_t nbufs)
@@ -568,10 +619,11 @@ size_t shuffle_dense_lds_bytes(uint32_t N, uint32_t nbufs)
     return (kStrip / 2 + static_cast<size_t>(N) * nbufs * kStrip) * sizeof(uint32_t);
 }
 
-hipError_t launch_shuffle_dense(const ShuffleArgs &a, hipStream_t stream, bool finish)
+hipError_t launch_shuffle_dense(const ShuffleArgs &a, hipStream_t stream)
 {
-    if (a.num_tiles == 0 || a.nsegs == 0) return finish ? finish_call(a, stream) : hipSuccess;
+    if (a.num_tiles == 0 || a.nsegs == 0) return nothing_to_launch(a, stream);
     if (a.nbufs == 0 || a.nbufs > kMaxBufs || a.tile_coords != kStrip) return hipErrorInvalidValue;
+    if (a.tickets != nullptr && a.expected == nullptr) return hipErrorInvalidValue;
     const size_t lds_bytes = shuffle_dense_lds_bytes(a.N, a.nbufs);
     // the direct-to-LDS loads address LDS through a 16-bit offset
     if (lds_bytes > 65536 || a.num_tiles > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
@@ -593,15 +645,12 @@ hipError_t launch_shuffle_dense(const ShuffleArgs &a, hipStream_t stream, bool f
         default: hipLaunchKernelGGL((shuffle_dense_kernel<4, false>), grid, block, lds_bytes, stream, a); break;
         }
     }
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess || !finish) return e;
-    return finish_call(a, stream);
+    return hipGetLastError();
 }
 
 hipError_t launch_shuffle_gap(const ShuffleArgs &a, hipStream_t stream)
 {
-    const bool finish = true;
-    if (a.num_tiles == 0 || a.nsegs == 0) return finish_call(a, stream);
+    if (a.num_tiles == 0 || a.nsegs == 0) return nothing_to_launch(a, stream);
     if (a.blocks_per_wave == 0 || a.blocks_per_wave > kWave || a.tile_coords != kGapPiece)
         return hipErrorInvalidValue;
     if ((a.blocks_per_wave & (a.blocks_per_wave - 1)) != 0) return hipErrorInvalidValue;   // lists share 512 slots evenly
@@ -611,18 +660,26 @@ hipError_t launch_shuffle_gap(const ShuffleArgs &a, hipStream_t stream)
     while (waves > 1 && per_wave * waves > 65536) waves >>= 1;
     if (per_wave * waves > 65536) return hipErrorInvalidConfiguration;
     const uint64_t nwaves = (a.num_tiles + a.blocks_per_wave - 1) / a.blocks_per_wave;
+    if (a.tickets != nullptr && (a.expected != nullptr || a.nwaves != nwaves)) return hipErrorInvalidValue;
     const uint64_t blocks64 = (nwaves + waves - 1) / waves;
     if (blocks64 > 0x7FFFFFFFull) return hipErrorInvalidConfiguration;
     const dim3 grid(static_cast<uint32_t>(blocks64)), block(kWave * waves);
-    switch (a.nbufs) {
-    case 1: hipLaunchKernelGGL(shuffle_gap_kernel<1>, grid, block, per_wave * waves, stream, a); break;
-    case 2: hipLaunchKernelGGL(shuffle_gap_kernel<2>, grid, block, per_wave * waves, stream, a); break;
-    case 3: hipLaunchKernelGGL(shuffle_gap_kernel<3>, grid, block, per_wave * waves, stream, a); break;
-    default: hipLaunchKernelGGL(shuffle_gap_kernel<4>, grid, block, per_wave * waves, stream, a); break;
+    if (a.stream_stores) {
+        switch (a.nbufs) {
+        case 1: hipLaunchKernelGGL((shuffle_gap_kernel<1, true>), grid, block, per_wave * waves, stream, a); break;
+        case 2: hipLaunchKernelGGL((shuffle_gap_kernel<2, true>), grid, block, per_wave * waves, stream, a); break;
+        case 3: hipLaunchKernelGGL((shuffle_gap_kernel<3, true>), grid, block, per_wave * waves, stream, a); break;
+        default: hipLaunchKernelGGL((shuffle_gap_kernel<4, true>), grid, block, per_wave * waves, stream, a); break;
+        }
+    } else {
+        switch (a.nbufs) {
+        case 1: hipLaunchKernelGGL((shuffle_gap_kernel<1, false>), grid, block, per_wave * waves, stream, a); break;
+        case 2: hipLaunchKernelGGL((shuffle_gap_kernel<2, false>), grid, block, per_wave * waves, stream, a); break;
+        case 3: hipLaunchKernelGGL((shuffle_gap_kernel<3, false>), grid, block, per_wave * waves, stream, a); break;
+        default: hipLaunchKernelGGL((shuffle_gap_kernel<4, false>), grid, block, per_wave * waves, stream, a); break;
+        }
     }
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess || !finish) return e;
-    return finish_call(a, stream);
+    return hipGetLastError();
 }
 
 }  // namespace wash

@@ -241,6 +241,41 @@ def test_shuffle_keeps_mean_and_multiset_on_device(wash):
     assert np.all(np.abs(after.cpu().numpy() - ref_avg) <= 1e-6 * scale)
 
 
+def test_calls_on_two_streams_do_not_share_scratch(wash):
+    """The selected count and the partial sums of the consensus distance go through library-owned device
+    memory that belongs to the calling stream: shuffles (both mask streams) and distance passes that
+    overlap on two streams give the oracle's counts, bits and sums."""
+    N = 6
+    cases = []
+    for k, (P, p, stream) in enumerate([(3_000_001, 0.02, "v1"), (2_500_003, 0.3, "v1"), (3_100_007, 0.01, "gap"),
+                                         (2_000_003, 0.05, "gap")]):
+        pop = (np.random.default_rng(70 + k).standard_normal((N, P)) * 0.02).astype(np.float32)
+        cases.append((pop, [(0, P // 2, p), (P // 2, P - P // 2, p / 2)], stream))
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    steps = 12
+    for a, b in ((0, 1), (2, 3), (0, 3)):
+        devs, cnts, dists = [], [], []
+        for idx in (a, b):
+            devs.append(torch.from_numpy(cases[idx][0]).cuda())
+            cnts.append(torch.zeros(1, dtype=torch.int64, device="cuda"))
+            dists.append(torch.zeros(N, dtype=torch.float64, device="cuda"))
+        torch.cuda.synchronize()
+        print(f"two streams: cases {a} and {b}", flush=True)
+        for step in range(steps):
+            for slot, idx in enumerate((a, b)):
+                with torch.cuda.stream(streams[slot]):
+                    _fn(wash, cases[idx][2])(devs[slot], None, cases[idx][1], 5, step, cnts[slot])
+                    wash.wash_consensus_sqdist(devs[slot], out=dists[slot])
+        torch.cuda.synchronize()
+        for slot, idx in enumerate((a, b)):
+            ref = cases[idx][0].copy()
+            ref_cnt = sum(oracle.shuffle(ref, None, cases[idx][1], 5, step, threads=8, stream=cases[idx][2])
+                          for step in range(steps))
+            assert int(cnts[slot].item()) == ref_cnt
+            assert np.array_equal(_bits(devs[slot].cpu().numpy()), _bits(ref))
+            assert np.allclose(dists[slot].cpu().numpy(), oracle.consensus_sqdist(ref), rtol=1e-10, atol=0)
+
+
 def test_error_paths_launch_nothing(wash):
     d = torch.zeros((2, 100), dtype=torch.float32, device="cuda")
     d.copy_(torch.arange(200, dtype=torch.float32, device="cuda").view(2, 100))
