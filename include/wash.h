@@ -14,15 +14,20 @@
  *
  * one host helper gives the layer-wise probabilities of Eq. 6, and two further
  * passes serve the paper's analysis: wash_consensus_sqdist (Eq. 2, Eq. 5) and
- * wash_weighted_average (interpolations between the models).
+ * wash_weighted_average (interpolations between the models).  Measurement
+ * aids (a plain copy, a scattered-access probe) are declared in wash_bench.h.
  *
  * Conventions for every entry point
  *   - "device" pointers are HIP device memory on the CURRENT device of the
  *     calling thread; "host" pointers are ordinary process memory.
  *   - The caller owns every buffer it passes.  The library allocates only a
- *     small internal device table per distinct segment list (cached) and one
- *     1 MiB scratch buffer per device for wash_consensus_sqdist, on first use;
- *     wash_shutdown() releases them.
+ *     small internal device table per distinct segment list (cached), and, per
+ *     stream that asks for a selected count, a step advance or a consensus
+ *     distance, one workspace of about 1 MiB (plus a few spare ones, for
+ *     streams under graph capture, which cannot allocate), on first use;
+ *     wash_shutdown() releases them.  Calls on different streams never share
+ *     a workspace; wash_consensus_sqdist_noalloc is the one call that uses a
+ *     fixed array instead.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls enqueue work on it and return without waiting; the usual stream
  *     ordering applies to the buffers.
@@ -203,8 +208,8 @@ int papa_ema(float *params, uint32_t N, uint64_t P, float alpha, void *stream);
  * reduction has a fixed shape: the same input gives the same bits every time.
  *   params  device, [N, P] fp32 (read only)    out  device, N doubles (overwritten)
  *   g_begin <= g_end <= P   (an empty slice gives zeros)
- * Uses 1 MiB of library-owned device scratch per device: calls that overlap on
- * one GPU (different streams) race on it.
+ * The partial sums live in the workspace of the calling stream, so calls on
+ * different streams do not interfere.
  * Errors: WASH_EINVAL for NULL pointers, N = 0 or > WASH_MAX_N, P = 0, a slice
  * outside [0, P]; WASH_EHIP if the scratch cannot be allocated or a launch fails.
  */
@@ -252,28 +257,6 @@ int wash_weighted_average(const float *params, const double *weights, float *out
  * Errors: WASH_EINVAL for p outside [0,1] or NaN, L = 0, unknown schedule, NULL out.
  */
 int wash_layer_probs(double p, uint32_t L, int schedule, double *out);
-
-/*
- * Measurement aid, not part of the method: dst[0..n) = src[0..n) with the same
- * 16-byte streaming access the average and the EMA use.  It reads 4n and writes
- * 4n bytes, which makes it the yardstick for the bandwidth a one-pass kernel
- * reaches on this chip and the known-size kernel that calibrates the HBM
- * traffic counters.   src, dst: device, n floats, not overlapping.
- * Errors: WASH_EINVAL for NULL pointers, n = 0, overlap.
- */
-int wash_copy_f32(const float *src, float *dst, uint64_t n, void *stream);
-
-/*
- * Measurement aid, not part of the method: the yardstick for the shuffle's memory phase.
- * Every thread of `blocks` x 256 threads does `rounds` rounds of 8 independent 4-byte accesses
- * to pseudo-random 128-byte lines of buf (mode 0: loads; 1: stores; 2: a load followed by a
- * store to the same word), i.e. blocks * 256 * rounds * 8 elements per call.  The contents of
- * buf are overwritten in modes 1 and 2.
- *   buf    device, lines * 128 bytes       lines  power of two, 2 .. 2^32
- * Errors: WASH_EINVAL for NULL buf, lines not a power of two, an unknown mode, rounds = 0,
- * blocks = 0 or > 2^20.
- */
-int wash_probe_scattered(float *buf, uint64_t lines, int mode, uint32_t rounds, uint32_t blocks, void *stream);
 
 /* Text for a status code (static storage, never NULL). */
 const char *wash_strerror(int status);

@@ -262,7 +262,7 @@ def wash_weighted_average(params: torch.Tensor, weights: Sequence[float],
 
 
 def wash_copy_f32(src: torch.Tensor, dst: torch.Tensor) -> None:
-    """Plain streaming copy of a float32 buffer (bandwidth yardstick, see wash.h)."""
+    """Plain streaming copy of a float32 buffer (bandwidth yardstick, see wash_bench.h)."""
     for t in (src, dst):
         if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
             raise TypeError("need contiguous float32 GPU tensors")
@@ -275,7 +275,7 @@ def wash_copy_f32(src: torch.Tensor, dst: torch.Tensor) -> None:
 
 def wash_probe_scattered(buf: torch.Tensor, mode: int, rounds: int, blocks: int) -> int:
     """Scattered 4-byte access yardstick on a float32 buffer of a power-of-two number of 128-byte lines
-    (see wash.h); returns the number of elements accessed."""
+    (see wash_bench.h); returns the number of elements accessed."""
     if not (buf.is_cuda and buf.dtype == torch.float32 and buf.is_contiguous()):
         raise TypeError("need a contiguous float32 GPU tensor")
     lines = buf.numel() // 32

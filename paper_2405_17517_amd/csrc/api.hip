@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "../../include/wash.h"
+#include "../../include/wash_bench.h"
 #include "gaplog.hpp"
 #include "kernels.hpp"
 

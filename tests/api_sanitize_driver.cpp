@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "../include/wash.h"
+#include "../include/wash_bench.h"
 
 static int failures = 0;
 #define CHECK(cond) do { if (!(cond)) { std::printf("FAILED line %d: %s\n", __LINE__, #cond); ++failures; } } while (0)
@@ -75,6 +76,11 @@ int main()
     w[3] = std::nan("");
     CHECK(wash_weighted_average(fake, w, fake2, 4, 100, nullptr) == WASH_EINVAL);
     CHECK(wash_consensus_sqdist(fake, 4, 100, 50, 40, reinterpret_cast<double *>(fake2), nullptr) == WASH_EINVAL);
+    CHECK(wash_consensus_sqdist_noalloc(fake, 4, 100, 50, 40, reinterpret_cast<double *>(fake2), nullptr) == WASH_EINVAL);
+    CHECK(wash_consensus_sqdist_noalloc(fake, 33, 100, 0, 40, reinterpret_cast<double *>(fake2), nullptr) == WASH_EINVAL);
+    CHECK(wash_set_option(WASH_OPT_SHUFFLE_BLOCKS_PER_CU, 21) == WASH_EINVAL);
+    CHECK(wash_set_option(WASH_OPT_SHUFFLE_BLOCKS_PER_CU, 4) == WASH_OK);
+    CHECK(wash_set_option(WASH_OPT_SHUFFLE_BLOCKS_PER_CU, 0) == WASH_OK);
     CHECK(wash_copy_f32(fake, fake + 10, 100, nullptr) == WASH_EINVAL);
     CHECK(wash_probe_scattered(fake, 3, 0, 1, 1, nullptr) == WASH_EINVAL);
     // options and texts

@@ -21,14 +21,18 @@ def lib():
 
 
 def _declared_functions():
-    src = open(os.path.join(ROOT, "include", "wash.h")).read()
-    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
-    return sorted(set(re.findall(r"\b(wash_[a-z_]+|papa_ema)\s*\(", src)))
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        src = open(os.path.join(ROOT, "include", header)).read()
+        src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+        names |= set(re.findall(r"\b(wash_[a-z_0-9]+|papa_ema)\s*\(", src))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_functions()
-    assert {"wash_shuffle", "wash_average", "papa_ema", "wash_layer_probs", "wash_strerror"} <= set(names)
+    assert {"wash_shuffle", "wash_average", "papa_ema", "wash_layer_probs", "wash_strerror", "wash_copy_f32",
+            "wash_consensus_sqdist_noalloc"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
