@@ -86,8 +86,13 @@ def kernel_rooflines(N, P, bufs, frac_selected, t_ms):
     return out
 
 
-def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, stream="v1", states=None):
-    """Time the hot path on one workload. Returns a dict of measurements."""
+_PLACEMENT = {}      # per run of this script: arena size, and the buffer offsets found for each config
+
+
+def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, stream="v1", states=None, placement="tuned"):
+    """Time the hot path on one workload. Returns a dict of measurements.
+    placement: "tuned" = the buffers sit where wash.place_population found one step fastest (populations from
+    1 GiB per buffer on); "default" = wherever torch's allocator puts them."""
     from workloads import device_population
 
     dev = "cuda:0"
@@ -95,7 +100,25 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
     N, P = cfg.N, cfg.P
     segs_list = cfg.segments(p_override)
     segs = wash.SegmentList(segs_list)
-    pop, mom = device_population(tensors, N, cfg.init, cfg.data_seed, cfg.momentum, dev)
+    place_info, placed = None, None
+    if placement == "tuned" and states is None and N * P * 4 >= (1 << 30):
+        # one arena of a fixed size per run of this script, so that positions found once can be used again
+        arena_bytes = _PLACEMENT.setdefault("arena_bytes", None)
+        try:
+            placed, place_info = wash.place_population(
+                N, P, 2 if cfg.momentum else 1, segs, dev, arena_bytes=arena_bytes, offsets=_PLACEMENT.get(cfg.index),
+                log=lambda m: print(f"[bench] placement, config {cfg.index}: {m}", file=sys.stderr, flush=True))
+            _PLACEMENT["arena_bytes"] = place_info["arena_bytes"]
+            _PLACEMENT[cfg.index] = place_info["offsets"]
+        except (MemoryError, RuntimeError, ValueError) as exc:
+            print(f"[bench] placement skipped ({exc}); buffers from the default allocator", file=sys.stderr, flush=True)
+            placed, place_info = None, None
+            torch.cuda.empty_cache()
+    if placed is not None:
+        pop, mom = device_population(tensors, N, cfg.init, cfg.data_seed, cfg.momentum, dev,
+                                     out=(placed[0], placed[1] if cfg.momentum else None))
+    else:
+        pop, mom = device_population(tensors, N, cfg.init, cfg.data_seed, cfg.momentum, dev)
     bufs = 2 if cfg.momentum else 1
     state_bufs = None
     if states is not None:
@@ -188,7 +211,7 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
 
     # the same step captured once in a HIP graph and replayed; the shuffle reads its step number from
     # device memory and advances it, so every replay is a new iteration (fresh mask and permutations)
-    graph_ms = None
+    graph_ms, graph_bufs = None, None
     try:
         step_dev = torch.full((1,), step_no[0], dtype=torch.int64, device=dev)
         graph_bufs = state_bufs if state_bufs is not None else ([pop, mom] if mom is not None else [pop])
@@ -233,7 +256,12 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
         "cache_resident": N * P * 4 * bufs <= 256 * (1 << 20),
         "roofline": kernel_rooflines(N, P, bufs, frac_sel, avg_ms),
         "analysis_passes": extra,
+        "placement": ({"tuned": place_info["tuned"], "arena_GiB": place_info["arena_bytes"] / 2**30,
+                       "offsets_GiB": [o / 2**30 for o in place_info["offsets"]],
+                       "probes_ms": [[(o / 2**30, round(ms, 3)) for o, ms in t] for t in place_info["probes_ms"]]}
+                      if place_info is not None else {"tuned": False}),
     }
+    place_info = placed = state_bufs = graph_bufs = None
     del pop, mom, ema_buf, out
     torch.cuda.empty_cache()
     return res
@@ -433,6 +461,13 @@ def main():
                     help="cap on resident blocks per compute unit of the gathering shuffle kernel (0 = none)")
     ap.add_argument("--dense", type=int, default=None, choices=[0, 1, 2],
                     help="wash_shuffle's dense path: 0 automatic, 1 never, 2 whenever it fits")
+    ap.add_argument("--placement", choices=["tuned", "default"], default="tuned",
+                    help="tuned: buffers of 1 GiB and more are placed by wash.place_population (one arena, the "
+                         "position where a step runs fastest); default: torch's allocator")
+    ap.add_argument("--placement-from", default=None,
+                    help="detail file of an earlier run of this script: use the arena size and buffer offsets it found "
+                         "instead of probing again (for runs under a profiler, where probe launches would mix into "
+                         "the per-kernel statistics)")
     ap.add_argument("--only", choices=["pass", "copy"], default="pass",
                     help="copy: run only the copy yardstick (for counter calibration)")
     args = ap.parse_args()
@@ -471,10 +506,14 @@ def main():
     def note(msg):
         print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
+    if args.placement_from:
+        with open(args.placement_from) as f:
+            earlier = json.load(f).get("placement_found", {})
+        _PLACEMENT.update({(int(k) if k.isdigit() else k): v for k, v in earlier.items()})
     cfg = get_config(args.config)
     note(f"headline workload: config {cfg.index} ({cfg.name}), N={cfg.N}, P={cfg.P}")
     main_res = run_config(torch, wash, cfg, args.steps, args.warmup, p_override=args.p, count=not args.no_count,
-                          stream=args.stream, states=args.states)
+                          stream=args.stream, states=args.states, placement=args.placement)
     note(f"config {cfg.index}: shuffle {main_res['avg_us']['wash_shuffle']:.1f} us, ema "
          f"{main_res['avg_us']['papa_ema']:.1f} us, average {main_res['avg_us']['wash_average']:.1f} us")
     yard = copy_yardstick(torch, wash)
@@ -519,8 +558,9 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"config {cfg.index}: {cfg.name}, N={cfg.N}, P={cfg.P}, {p_text}, "
                                f"{'params+momentum' if cfg.momentum else 'params only'}, "
-                               f"{main_res['population_bytes'] / 1e9:.1f} GB in HBM; step = wash_shuffle + papa_ema + "
-                               "wash_average; value = P / wash_shuffle time"},
+                               f"{main_res['population_bytes'] / 1e9:.1f} GB in HBM"
+                               f"{' (buffers placed by place_population)' if main_res['placement']['tuned'] else ''}; "
+                               "step = wash_shuffle + papa_ema + wash_average; value = P / wash_shuffle time"},
         "pass_coords_per_s": _r(main_res["pass_coords_per_s"], 5),
         "selected_per_step": main_res["selected_per_step"],
         "roofline": roofline,
@@ -545,7 +585,8 @@ def main():
                     if c.index == cfg.index and st == args.stream:
                         res = dict(main_res)
                     else:
-                        res = run_config(torch, wash, c, k, min(args.warmup, 3), p_override=p, stream=st)
+                        res = run_config(torch, wash, c, k, min(args.warmup, 3), p_override=p, stream=st,
+                                         placement=args.placement)
                     res["p_override"] = p
                     is_dense = st == "v1" and (p if p is not None else 0.0) >= 0.08
                     res["roofline"]["wash_shuffle"]["bound"] = bound_label(c.N, res["buffers_shuffled"],
@@ -568,6 +609,7 @@ def main():
                      f"{b['shuffle_all_cores']['coords_per_s']:.3g} coords/s ({b['shuffle_all_cores']['threads']} threads)")
             detail["cpu_baseline_per_config"] = per_cfg
 
+    detail["placement_found"] = {str(k): v for k, v in _PLACEMENT.items()}
     if args.detail:
         try:
             os.makedirs(os.path.dirname(args.detail), exist_ok=True)

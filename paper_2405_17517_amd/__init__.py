@@ -5,3 +5,4 @@ from .binding import (  # noqa: F401
     MAX_N, OPT_AVERAGE_CHUNKS, OPT_DENSE, OPT_GAP_BLOCKS, OPT_SHUFFLE_BLOCKS_PER_CU, OPT_STREAM_MIN_BYTES, OPT_TILE_COORDS, SegmentList, WashError, papa_ema, wash_average, wash_consensus_sqdist, wash_consensus_sqdist_noalloc, wash_copy_f32, wash_probe_scattered, wash_weighted_average, wash_layer_probs,
     wash_set_option, wash_shuffle, wash_shuffle_gap, wash_shuffle_device_step, wash_shuffle_states, wash_shutdown,
 )
+from .placement import place_population  # noqa: F401,E402

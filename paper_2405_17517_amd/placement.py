@@ -1,0 +1,129 @@
+"""Where the [N, P] buffers of a population sit in HBM (MI355X).
+
+The scattered stores of the shuffling step (Eq. 3 moves single values across the N
+rows) run at the rate the DRAM banks under the buffers can take, and that depends on
+the physical place of the buffers: measured on MI355X, one 32.8 GiB population takes
+7.3 ms per shuffle when it lies inside one of the large regions the physical address
+space is divided into (64, 64, 32, 32, 32 ... GiB from the start of a big allocation)
+and 5.8 ms when it straddles a region boundary; parameters and momentum side by side
+in one region take 13.6 - 14.2 ms, in different regions 10.9 - 11.0 ms.  Virtual
+addresses tell nothing about this, and the default allocator places buffers back to
+back.
+
+`place_population` therefore allocates ONE arena, tries positions for the buffers on a
+coarse grid and keeps the fastest, timing the library's own kernels on the (still
+uninitialised) memory.  It returns ordinary contiguous [N, P] float32 views: the
+layout every entry point of the library expects is unchanged.  This module holds no
+arithmetic of the method; torch is used for device memory and events only.
+"""
+from typing import Callable, List, Optional, Sequence, Tuple
+
+import torch
+
+from . import binding as _b
+
+GiB = 1 << 30
+
+
+def _timed(fn: Callable[[], None], reps: int) -> float:
+    fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def place_population(N: int, P: int, nbuf: int = 1, segs=None, device: str = "cuda:0",
+                     arena_bytes: Optional[int] = None, reserve_bytes: int = 24 * GiB, grid_bytes: int = 8 * GiB,
+                     reps: int = 2, log: Optional[Callable[[str], None]] = None,
+                     offsets: Optional[Sequence[int]] = None) -> Tuple[List[torch.Tensor], dict]:
+    """nbuf uninitialised [N, P] float32 buffers (parameters first, then optimizer states) inside one arena,
+    at the positions where one shuffling step over them (plus one average of the parameters) ran fastest.
+
+      segs           the segment list the caller will shuffle with (list of (offset, length, p) or a
+                     SegmentList); default: one segment with p = 0.02
+      arena_bytes    size of the arena; default: the free device memory minus reserve_bytes
+      grid_bytes     spacing of the candidate positions
+      offsets        byte offsets found by an earlier call with the same arena size: the buffers are placed
+                     there without probing
+    Returns (buffers, info); info holds the arena tensor (keep it alive as long as the buffers), the chosen
+    offsets, and the probe times in ms of every candidate.  The buffers are placed one after the other: the
+    parameters where they alone are fastest, then each further buffer where the step over all buffers
+    placed so far is fastest.  Populations too small to matter (below 1 GiB per buffer) and arenas without
+    room to move are placed back to back without probing."""
+    dev = torch.device(device)
+    buf_bytes = N * P * 4
+    pitch = (buf_bytes + 255) // 256 * 256
+    with torch.cuda.device(dev):
+        torch.cuda.empty_cache()                    # blocks torch keeps cached count as used otherwise
+        free, _ = torch.cuda.mem_get_info()
+    if arena_bytes is None:
+        arena_bytes = free - reserve_bytes
+    arena_bytes = min(arena_bytes, free - (1 << 28))
+    if arena_bytes < nbuf * pitch:
+        raise MemoryError(f"{nbuf} buffers of {buf_bytes} bytes do not fit an arena of {arena_bytes} bytes")
+    arena = torch.empty(arena_bytes, dtype=torch.uint8, device=dev)
+    if arena.data_ptr() % 256 != 0:
+        raise RuntimeError("arena is not 256-byte aligned")
+
+    def view(off: int) -> torch.Tensor:
+        return arena[off:off + buf_bytes].view(torch.float32).view(N, P)
+
+    info = {"arena": arena, "arena_bytes": arena_bytes, "offsets": [], "probes_ms": [], "tuned": False}
+    if offsets is not None:
+        offs = [int(o) for o in offsets]
+        if len(offs) != nbuf or any(o % 256 != 0 or o < 0 or o + buf_bytes > arena_bytes for o in offs) or \
+                any(a < b + pitch and b < a + pitch for i, a in enumerate(offs) for b in offs[:i]):
+            raise ValueError("offsets do not fit this arena")
+        info["offsets"], info["tuned"] = offs, True
+        return [view(o) for o in offs], info
+    candidates = list(range(0, arena_bytes - pitch + 1, grid_bytes))
+    if buf_bytes < GiB or len(candidates) < 2 * nbuf + 1:
+        offs = [k * pitch for k in range(nbuf)]
+        info["offsets"] = offs
+        return [view(o) for o in offs], info
+
+    if segs is None:
+        segs = [(0, P, 0.02)]
+    if not isinstance(segs, _b.SegmentList):
+        segs = _b.SegmentList(segs)
+    arena.zero_()                                   # the probes move whatever is there: keep it finite
+    out = torch.empty(P, dtype=torch.float32, device=dev)
+    step = [0]
+    chosen: List[int] = []
+
+    def overlaps(o: int) -> bool:
+        return any(o < c + pitch and c < o + pitch for c in chosen)
+
+    for k in range(nbuf):
+        best, best_ms, table = None, float("inf"), []
+        for o in candidates:
+            if overlaps(o):
+                continue
+            bufs = [view(c) for c in chosen] + [view(o)]
+
+            def probe():
+                _b.wash_shuffle_states(bufs, segs, 0, step[0])
+                step[0] += 1
+                _b.wash_average(bufs[0], out)
+
+            ms = _timed(probe, reps)
+            table.append((o, ms))
+            if ms < best_ms:
+                best, best_ms = o, ms
+        if best is None:
+            raise MemoryError("no room left in the arena")
+        chosen.append(best)
+        info["probes_ms"].append(table)
+        if log is not None:
+            worst = max(ms for _, ms in table)
+            log(f"buffer {k}: offset {best / GiB:.0f} GiB of the arena, step {best_ms:.2f} ms "
+                f"(candidates {min(ms for _, ms in table):.2f} .. {worst:.2f} ms)")
+    info["offsets"] = chosen
+    info["tuned"] = True
+    del out
+    return [view(o) for o in chosen], info

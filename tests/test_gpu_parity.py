@@ -454,3 +454,33 @@ def test_dense_and_sparse_paths_give_the_oracle_bits(wash, N, P, nbuf, p, dense)
     assert int(cnt.item()) == ref_cnt
     for d, r in zip(dev, refs):
         assert np.array_equal(_bits(d.cpu().numpy()), _bits(r))
+
+
+def test_place_population_returns_ordinary_buffers(wash):
+    """Buffers handed out by the placement helper (one arena, positions chosen by timing the library's own
+    kernels) are plain contiguous [N, P] tensors: disjoint, inside the arena, and a shuffling step with
+    momentum on them gives the oracle's bits."""
+    N, P = 4, 70_000_003                      # 1.12 GB per buffer: large enough for the helper to probe
+    segs = [(0, P // 2, 0.01), (P // 2, P - P // 2, 0.002)]
+    bufs, info = wash.place_population(N, P, 2, segs, arena_bytes=6 << 30, grid_bytes=512 << 20)
+    assert info["tuned"] and len(bufs) == 2 and len(info["probes_ms"]) == 2
+    a0 = info["arena"].data_ptr()
+    spans = []
+    for b in bufs:
+        assert b.shape == (N, P) and b.dtype == torch.float32 and b.is_contiguous() and b.data_ptr() % 256 == 0
+        assert a0 <= b.data_ptr() and b.data_ptr() + N * P * 4 <= a0 + info["arena_bytes"]
+        spans.append((b.data_ptr(), b.data_ptr() + N * P * 4))
+    assert spans[0][1] <= spans[1][0] or spans[1][1] <= spans[0][0]
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    bufs[0].normal_(0.0, 0.02, generator=gen)
+    bufs[1].normal_(0.0, 1e-3, generator=gen)
+    ref, refm = bufs[0].cpu().numpy(), bufs[1].cpu().numpy()
+    cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+    wash.wash_shuffle(bufs[0], bufs[1], segs, 3, 7, cnt)
+    ref_cnt = oracle.shuffle(ref, refm, segs, 3, 7, threads=8)
+    assert int(cnt.item()) == ref_cnt
+    assert np.array_equal(_bits(bufs[0].cpu().numpy()), _bits(ref))
+    assert np.array_equal(_bits(bufs[1].cpu().numpy()), _bits(refm))
+    # small populations are placed back to back without probing
+    small, sinfo = wash.place_population(3, 1000, 2, arena_bytes=1 << 20)
+    assert not sinfo["tuned"] and small[0].shape == (3, 1000) and small[1].data_ptr() >= small[0].data_ptr() + 12000

@@ -67,15 +67,21 @@ def host_population(tensors: Sequence[Tensor], N: int, init: str, seed: int,
 
 
 def device_population(tensors: Sequence[Tensor], N: int, init: str, seed: int,
-                      momentum: bool = False, device: str = "cuda:0"):
+                      momentum: bool = False, device: str = "cuda:0", out=None):
     """torch float32 [N, P] (and momentum or None) generated on the device with
-    torch's own seeded generator, in place, tensor by tensor (no host copy)."""
+    torch's own seeded generator, in place, tensor by tensor (no host copy).
+    out: optional (params, momentum) [N, P] float32 device tensors to fill instead of
+    allocating new ones (the values do not depend on where the buffers are)."""
     import torch
 
     gen = torch.Generator(device=device)
     gen.manual_seed(seed)
     P = sum(t.numel for t in tensors)
-    pop = torch.empty((N, P), dtype=torch.float32, device=device)
+    if out is not None:
+        pop = out[0]
+        assert tuple(pop.shape) == (N, P) and pop.dtype == torch.float32 and pop.is_contiguous()
+    else:
+        pop = torch.empty((N, P), dtype=torch.float32, device=device)
     off = 0
     chunk = 1 << 26
     for t in tensors:
@@ -99,7 +105,11 @@ def device_population(tensors: Sequence[Tensor], N: int, init: str, seed: int,
         off += t.numel
     mom = None
     if momentum:
-        mom = torch.empty((N, P), dtype=torch.float32, device=device)
+        if out is not None:
+            mom = out[1]
+            assert tuple(mom.shape) == (N, P) and mom.dtype == torch.float32 and mom.is_contiguous()
+        else:
+            mom = torch.empty((N, P), dtype=torch.float32, device=device)
         for a in range(0, P, chunk):
             mom[:, a:min(a + chunk, P)].normal_(0.0, MOMENTUM_STD, generator=gen)
     return pop, mom
