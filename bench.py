@@ -92,7 +92,7 @@ _PLACEMENT = {}      # per run of this script: arena size, and the buffer offset
 def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, stream="v1", states=None, placement="tuned"):
     """Time the hot path on one workload. Returns a dict of measurements.
     placement: "tuned" = the buffers sit where wash.place_population found one step fastest (populations from
-    1 GiB per buffer on); "default" = wherever torch's allocator puts them."""
+    512 MiB per buffer on); "default" = wherever torch's allocator puts them."""
     from workloads import device_population
 
     dev = "cuda:0"
@@ -101,7 +101,7 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
     segs_list = cfg.segments(p_override)
     segs = wash.SegmentList(segs_list)
     place_info, placed = None, None
-    if placement == "tuned" and states is None and N * P * 4 >= (1 << 30):
+    if placement == "tuned" and states is None and N * P * 4 >= (1 << 29):
         # one arena of a fixed size per run of this script, so that positions found once can be used again
         arena_bytes = _PLACEMENT.setdefault("arena_bytes", None)
         try:
@@ -462,7 +462,7 @@ def main():
     ap.add_argument("--dense", type=int, default=None, choices=[0, 1, 2],
                     help="wash_shuffle's dense path: 0 automatic, 1 never, 2 whenever it fits")
     ap.add_argument("--placement", choices=["tuned", "default"], default="tuned",
-                    help="tuned: buffers of 1 GiB and more are placed by wash.place_population (one arena, the "
+                    help="tuned: buffers of 512 MiB and more are placed by wash.place_population (one arena, the "
                          "position where a step runs fastest); default: torch's allocator")
     ap.add_argument("--placement-from", default=None,
                     help="detail file of an earlier run of this script: use the arena size and buffer offsets it found "

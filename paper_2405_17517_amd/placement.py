@@ -53,7 +53,7 @@ def place_population(N: int, P: int, nbuf: int = 1, segs=None, device: str = "cu
     Returns (buffers, info); info holds the arena tensor (keep it alive as long as the buffers), the chosen
     offsets, and the probe times in ms of every candidate.  The buffers are placed one after the other: the
     parameters where they alone are fastest, then each further buffer where the step over all buffers
-    placed so far is fastest.  Populations too small to matter (below 1 GiB per buffer) and arenas without
+    placed so far is fastest.  Populations too small to matter (below 512 MiB per buffer) and arenas without
     room to move are placed back to back without probing."""
     dev = torch.device(device)
     buf_bytes = N * P * 4
@@ -82,7 +82,7 @@ def place_population(N: int, P: int, nbuf: int = 1, segs=None, device: str = "cu
         info["offsets"], info["tuned"] = offs, True
         return [view(o) for o in offs], info
     candidates = list(range(0, arena_bytes - pitch + 1, grid_bytes))
-    if buf_bytes < GiB or len(candidates) < 2 * nbuf + 1:
+    if buf_bytes < GiB // 2 or len(candidates) < 2 * nbuf + 1:
         offs = [k * pitch for k in range(nbuf)]
         info["offsets"] = offs
         return [view(o) for o in offs], info
