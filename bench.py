@@ -267,6 +267,30 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
     return res
 
 
+def padded_rows(torch, wash, cfg, reps=10):
+    """papa_ema and wash_average on the same population with every row padded to a multiple of 32 elements (128 bytes):
+    what the unaligned row pitch of this configuration costs the streaming kernels."""
+    N, P = cfg.N, (cfg.P + 31) // 32 * 32
+    pop = torch.empty(N, P, dtype=torch.float32, device="cuda:0").normal_(0.0, 0.02)
+    out = torch.empty(P, dtype=torch.float32, device="cuda:0")
+    res = {"N": N, "P_padded": P}
+    for name, fn, nbytes in (("papa_ema", lambda: wash.papa_ema(pop, cfg.alpha), 2.0 * N * P * 4),
+                             ("wash_average", lambda: wash.wash_average(pop, out), (N + 1.0) * P * 4)):
+        for _ in range(2):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        ms = a.elapsed_time(b) / reps
+        res[name] = {"avg_us": ms * 1e3, "frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    del pop, out
+    torch.cuda.empty_cache()
+    return res
+
+
 def copy_yardstick(torch, wash, n_floats=1 << 28, reps=10):
     src = torch.empty(n_floats, dtype=torch.float32, device="cuda:0").normal_()
     dst = torch.empty_like(src)
@@ -600,6 +624,14 @@ def main():
                          f"({res['roofline']['papa_ema']['frac'] * 100:.1f} %), average "
                          f"{res['avg_us']['wash_average']:.1f} us ({res['roofline']['wash_average']['frac'] * 100:.1f} %)")
         detail["all_configs"] = rows
+        detail["rows_padded_to_128_bytes"] = {}
+        for c in CONFIGS:
+            if c.P % 32 != 0 and c.N * c.P * 4 >= (256 << 20):
+                r = padded_rows(torch, wash, c)
+                detail["rows_padded_to_128_bytes"][f"config{c.index}"] = r
+                note(f"config {c.index} with rows padded to 128 bytes: ema {r['papa_ema']['avg_us']:.1f} us "
+                     f"({r['papa_ema']['frac'] * 100:.1f} %), average {r['wash_average']['avg_us']:.1f} us "
+                     f"({r['wash_average']['frac'] * 100:.1f} %)")
         if not args.no_cpu_baseline:
             per_cfg = {}
             for c in CONFIGS:

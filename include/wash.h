@@ -96,6 +96,12 @@ typedef struct wash_segment {
  *                   any element of such a strip with the value it already has;
  *                   see WASH_OPT_DENSE.)
  *   nsegs           number of segments (0 allowed: nothing happens)
+ *                   (A list seen for the first time costs one device allocation and
+ *                   one blocking copy of a small table; the 16 most recent lists per
+ *                   process are kept, and dropping an older one waits for the
+ *                   device.  The paper's probabilities do not change over the
+ *                   iterations; a caller that changes them every step pays this
+ *                   every step.)
  *   seed, step      stream address; step < 2^32
  *   selected_count  device uint64 or NULL; the number of selected coordinates
  *                   (the per-model communication volume of Sec. 3) is ADDED to it
