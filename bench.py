@@ -540,6 +540,13 @@ def main():
                           stream=args.stream, states=args.states, placement=args.placement)
     note(f"config {cfg.index}: shuffle {main_res['avg_us']['wash_shuffle']:.1f} us, ema "
          f"{main_res['avg_us']['papa_ema']:.1f} us, average {main_res['avg_us']['wash_average']:.1f} us")
+    # the same workload with the buffers wherever torch's allocator puts them, reported beside the placed run
+    plain_res = None
+    if main_res["placement"]["tuned"]:
+        plain_res = run_config(torch, wash, cfg, args.steps, args.warmup, p_override=args.p, count=not args.no_count,
+                               stream=args.stream, states=args.states, placement="default")
+        note(f"config {cfg.index}, allocator's placement: shuffle {plain_res['avg_us']['wash_shuffle']:.1f} us, ema "
+             f"{plain_res['avg_us']['papa_ema']:.1f} us, average {plain_res['avg_us']['wash_average']:.1f} us")
     yard = copy_yardstick(torch, wash)
     scat = scatter_yardstick(torch, wash)
 
@@ -591,8 +598,10 @@ def main():
         "roofline_per_kernel": per_kernel,
         "cpu_baseline": cpu,
     }
+    if plain_res is not None:
+        line["allocator_placement_us"] = {k: _r(v) for k, v in plain_res["avg_us"].items()}
 
-    detail = {"headline": line, "headline_detail": main_res, "copy_yardstick": yard, "scatter_yardstick": scat,
+    detail = {"headline": line, "headline_detail": main_res, "headline_allocator_placement": plain_res, "copy_yardstick": yard, "scatter_yardstick": scat,
               "shuffle_vs_scattered_stores": {
                   "bound": "scattered-store", "achieved": main_res["shuffle_store_units_per_s"] / 1e9,
                   "peak": scat["stores_Gelem_per_s"], "unit": "G half-lines/s",
