@@ -16,8 +16,8 @@ by wash_shuffle per second, ms_per_step = the whole pass, `roofline` for the
 kernel with the longest duration plus one entry per kernel, and the CPU oracle
 timed on a bounded sample of the same workload.  Everything else (per-kernel
 medians, yardsticks, every other configuration with both mask streams, the
-oracle timed on each configuration) goes to a side file, by default
-gpurun_out/bench_detail.json, and as progress lines to stderr.
+oracle timed on each configuration) goes to a side file (--detail PATH, an
+empty PATH for none), and as progress lines to stderr.
 """
 import argparse
 import json
