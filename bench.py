@@ -308,11 +308,12 @@ def copy_yardstick(torch, wash, n_floats=1 << 28, reps=10):
 
 
 def scatter_yardstick(torch, wash, lines=1 << 25, blocks=8192, rounds=16):
-    """G elements/s of independent scattered 4-byte loads, stores and load->store pairs on a 4 GiB buffer:
-    what the memory system gives a sparse shuffle that does nothing but touch its values."""
+    """G places/s of independent scattered 4-byte loads, stores and load->store pairs, and of stores of whole
+    64-byte pieces, on a 4 GiB buffer: what the memory system gives a sparse shuffle that does nothing but
+    touch its values."""
     buf = torch.zeros(lines * 32, dtype=torch.float32, device="cuda:0")
     out = {}
-    for mode, name in ((0, "loads"), (1, "stores"), (2, "load_then_store")):
+    for mode, name in ((0, "loads"), (1, "stores"), (2, "load_then_store"), (3, "stores_of_64_byte_pieces")):
         wash.wash_probe_scattered(buf, mode, rounds, blocks)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()

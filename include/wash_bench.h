@@ -28,11 +28,14 @@ int wash_copy_f32(const float *src, float *dst, uint64_t n, void *stream);
  * the yardstick for the shuffle's memory phase.
  * Every thread of `blocks` x 256 threads does `rounds` rounds of 8 independent 4-byte accesses
  * to pseudo-random 128-byte lines of buf (mode 0: loads; 1: stores; 2: a load followed by a
- * store to the same word), i.e. blocks * 256 * rounds * 8 elements per call.  The contents of
- * buf are overwritten in modes 1 and 2.
- *   buf    device, lines * 128 bytes       lines  power of two, 2 .. 2^32
+ * store to the same word), i.e. blocks * 256 * rounds * 8 elements per call.  Mode 3 stores whole
+ * 64-byte pieces instead: four neighbouring threads write 16 bytes each to one pseudo-random
+ * half line, blocks * 64 * rounds * 8 pieces per call (the memory side takes a whole piece
+ * without reading it first; a 4-byte store makes it fetch the piece).  The contents of buf are
+ * overwritten in modes 1 to 3.
+ *   buf    device, lines * 128 bytes (16-byte aligned for mode 3)       lines  power of two, 2 .. 2^32
  * Errors: WASH_EINVAL for NULL buf, lines not a power of two, an unknown mode, rounds = 0,
- * blocks = 0 or > 2^20.
+ * blocks = 0 or > 2^20, a misaligned buf in mode 3.
  */
 int wash_probe_scattered(float *buf, uint64_t lines, int mode, uint32_t rounds, uint32_t blocks, void *stream);
 

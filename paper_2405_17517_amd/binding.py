@@ -274,8 +274,9 @@ def wash_copy_f32(src: torch.Tensor, dst: torch.Tensor) -> None:
 
 
 def wash_probe_scattered(buf: torch.Tensor, mode: int, rounds: int, blocks: int) -> int:
-    """Scattered 4-byte access yardstick on a float32 buffer of a power-of-two number of 128-byte lines
-    (see wash_bench.h); returns the number of elements accessed."""
+    """Scattered access yardstick on a float32 buffer of a power-of-two number of 128-byte lines
+    (see wash_bench.h); returns the number of places accessed (4-byte elements in modes 0 to 2, 64-byte
+    pieces in mode 3)."""
     if not (buf.is_cuda and buf.dtype == torch.float32 and buf.is_contiguous()):
         raise TypeError("need a contiguous float32 GPU tensor")
     lines = buf.numel() // 32
@@ -284,7 +285,7 @@ def wash_probe_scattered(buf: torch.Tensor, mode: int, rounds: int, blocks: int)
     with torch.cuda.device(buf.device):
         rc = _lib.wash_probe_scattered(buf.data_ptr(), lines, int(mode), int(rounds), int(blocks), _stream(buf))
     _check(rc, "wash_probe_scattered")
-    return blocks * 256 * rounds * 8
+    return blocks * 256 * rounds * 8 // (4 if int(mode) == 3 else 1)
 
 
 def wash_layer_probs(p: float, L: int, schedule: int = 0):

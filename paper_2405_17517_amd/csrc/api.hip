@@ -637,7 +637,8 @@ int wash_probe_scattered(float *buf, uint64_t lines, int mode, uint32_t rounds, 
     if (buf == nullptr) return fail(WASH_EINVAL, "buf is NULL");
     if (lines < 2 || (lines & (lines - 1)) != 0 || lines > (1ull << 32))
         return fail(WASH_EINVAL, "lines must be a power of two in [2, 2^32]");
-    if (mode < 0 || mode > 2) return fail(WASH_EINVAL, "mode must be 0, 1 or 2");
+    if (mode < 0 || mode > 3) return fail(WASH_EINVAL, "mode must be 0, 1, 2 or 3");
+    if (mode == 3 && reinterpret_cast<uintptr_t>(buf) % 16 != 0) return fail(WASH_EINVAL, "mode 3 needs a 16-byte aligned buf");
     if (rounds == 0 || blocks == 0 || blocks > (1u << 20)) return fail(WASH_EINVAL, "rounds >= 1, 1 <= blocks <= 2^20");
     // the last word of the buffer takes the (never written) sink of the load-only mode
     uint32_t *words = reinterpret_cast<uint32_t *>(buf);

@@ -161,7 +161,9 @@ __global__ __launch_bounds__(kWave) void sqdist_final_kernel(const double *__res
 
 // Yardstick for the shuffle: independent 4-byte accesses to pseudo-random 128-byte lines of a
 // large buffer, 8 per thread and round.  mode 0: loads only; 1: stores only; 2: load, then store a
-// value to the same place (the access pattern of a sparse shuffle without any of its arithmetic).
+// value to the same place (the access pattern of a sparse shuffle without any of its arithmetic);
+// 3: stores of whole 64-byte pieces (four neighbouring threads write 16 bytes each to one
+// pseudo-random half line): the memory side takes these without filling the piece first.
 __device__ __forceinline__ uint32_t probe_mix(uint32_t x)
 {
     x ^= x >> 16;
@@ -172,6 +174,8 @@ __device__ __forceinline__ uint32_t probe_mix(uint32_t x)
     return x;
 }
 
+typedef uint32_t u4a __attribute__((ext_vector_type(4)));
+
 template <int MODE>
 __global__ __launch_bounds__(kThreads) void scatter_probe_kernel(uint32_t *__restrict__ buf, uint32_t line_mask,
                                                                  uint32_t rounds, uint32_t *__restrict__ sink)
@@ -179,6 +183,21 @@ __global__ __launch_bounds__(kThreads) void scatter_probe_kernel(uint32_t *__res
     constexpr int K = 8;
     const uint32_t tid = blockIdx.x * kThreads + threadIdx.x;
     uint32_t acc = tid;
+    if (MODE == 3) {
+        const uint32_t group = tid >> 2, part = tid & 3u;
+        for (uint32_t r = 0; r < rounds; ++r) {
+#pragma unroll
+            for (int k = 0; k < K; ++k) {
+                const uint32_t h = probe_mix(group * 2654435761u + r * 40503u + k * 0x9E3779B9u);
+                const uint32_t line = h & line_mask;
+                const uint32_t half = probe_mix(h) & 1u;
+                u4a *p = reinterpret_cast<u4a *>(buf + static_cast<uint64_t>(line) * 32u + half * 16u) + part;
+                const u4a v = {h, h + 1u, h + 2u, h + 3u};
+                *p = v;
+            }
+        }
+        return;
+    }
     for (uint32_t r = 0; r < rounds; ++r) {
         uint32_t *p[K];
         uint32_t v[K];
@@ -247,6 +266,7 @@ hipError_t launch_scatter_probe(uint32_t *buf, uint64_t lines, int mode, uint32_
     case 0: hipLaunchKernelGGL(scatter_probe_kernel<0>, dim3(blocks), dim3(kThreads), 0, stream, buf, mask, rounds, sink); break;
     case 1: hipLaunchKernelGGL(scatter_probe_kernel<1>, dim3(blocks), dim3(kThreads), 0, stream, buf, mask, rounds, sink); break;
     case 2: hipLaunchKernelGGL(scatter_probe_kernel<2>, dim3(blocks), dim3(kThreads), 0, stream, buf, mask, rounds, sink); break;
+    case 3: hipLaunchKernelGGL(scatter_probe_kernel<3>, dim3(blocks), dim3(kThreads), 0, stream, buf, mask, rounds, sink); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
