@@ -276,6 +276,48 @@ def test_calls_on_two_streams_do_not_share_scratch(wash):
             assert np.allclose(dists[slot].cpu().numpy(), oracle.consensus_sqdist(ref), rtol=1e-10, atol=0)
 
 
+def test_host_threads_on_their_own_streams(wash):
+    """Four host threads, each with a stream and a population of its own, call the library at the same time
+    (ctypes releases the interpreter lock during a call): the cached tables and the per-stream workspaces are
+    shared state of the library, and every thread must still get the oracle's bits, counts and sums."""
+    from concurrent.futures import ThreadPoolExecutor
+    N, steps = 5, 8
+    cases = []
+    for k, (P, p, stream) in enumerate([(1_200_001, 0.02, "v1"), (900_003, 0.2, "v1"), (1_100_007, 0.01, "gap"),
+                                         (1_200_001, 0.02, "gap")]):
+        pop = (np.random.default_rng(170 + k).standard_normal((N, P)) * 0.02).astype(np.float32)
+        cases.append((pop, [(0, P // 3, p), (P // 3, P - P // 3, p / 4)], stream))
+    devs = [torch.from_numpy(c[0]).cuda() for c in cases]
+    torch.cuda.synchronize()
+
+    def work(k):
+        pop, segs, which = cases[k]
+        s = torch.cuda.Stream()
+        cnt = torch.zeros(1, dtype=torch.int64, device="cuda")
+        with torch.cuda.stream(s):
+            cnt.zero_()
+            for step in range(steps):
+                _fn(wash, which)(devs[k], None, segs, 9, step, cnt)
+            dist = wash.wash_consensus_sqdist(devs[k])
+            mean = wash.wash_average(devs[k])
+            wash.papa_ema(devs[k], 0.9)
+        s.synchronize()
+        return int(cnt.item()), dist.cpu().numpy(), mean.cpu().numpy(), devs[k].cpu().numpy()
+
+    print("four threads", flush=True)
+    with ThreadPoolExecutor(max_workers=4) as pool:
+        results = list(pool.map(work, range(4)))
+    for k, (cnt, dist, mean, final) in enumerate(results):
+        pop, segs, which = cases[k]
+        ref = pop.copy()
+        ref_cnt = sum(oracle.shuffle(ref, None, segs, 9, step, threads=8, stream=which) for step in range(steps))
+        assert cnt == ref_cnt, k
+        assert np.allclose(dist, oracle.consensus_sqdist(ref), rtol=1e-10, atol=0), k
+        assert np.array_equal(_bits(mean), _bits(oracle.average(ref))), k
+        oracle.ema(ref, 0.9)
+        assert np.array_equal(_bits(final), _bits(ref)), k
+
+
 def test_error_paths_launch_nothing(wash):
     d = torch.zeros((2, 100), dtype=torch.float32, device="cuda")
     d.copy_(torch.arange(200, dtype=torch.float32, device="cuda").view(2, 100))
