@@ -542,8 +542,9 @@ def main():
     note(f"config {cfg.index}: shuffle {main_res['avg_us']['wash_shuffle']:.1f} us, ema "
          f"{main_res['avg_us']['papa_ema']:.1f} us, average {main_res['avg_us']['wash_average']:.1f} us")
     # the same workload with the buffers wherever torch's allocator puts them, reported beside the placed run
+    # (not under --placement-from: a traced run must hold the launches of one placement only)
     plain_res = None
-    if main_res["placement"]["tuned"]:
+    if main_res["placement"]["tuned"] and not args.placement_from:
         plain_res = run_config(torch, wash, cfg, args.steps, args.warmup, p_override=args.p, count=not args.no_count,
                                stream=args.stream, states=args.states, placement="default")
         note(f"config {cfg.index}, allocator's placement: shuffle {plain_res['avg_us']['wash_shuffle']:.1f} us, ema "
