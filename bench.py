@@ -107,9 +107,12 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
         try:
             placed, place_info = wash.place_population(
                 N, P, 2 if cfg.momentum else 1, segs, dev, arena_bytes=arena_bytes, offsets=_PLACEMENT.get(cfg.index),
+                boundaries=_PLACEMENT.get("boundaries"),
                 log=lambda m: print(f"[bench] placement, config {cfg.index}: {m}", file=sys.stderr, flush=True))
             _PLACEMENT["arena_bytes"] = place_info["arena_bytes"]
             _PLACEMENT[cfg.index] = place_info["offsets"]
+            if "boundaries" in place_info:
+                _PLACEMENT["boundaries"] = place_info["boundaries"]
         except (MemoryError, RuntimeError, ValueError) as exc:
             print(f"[bench] placement skipped ({exc}); buffers from the default allocator", file=sys.stderr, flush=True)
             placed, place_info = None, None
@@ -130,7 +133,9 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
         state_bufs = state_bufs[:states]
         bufs = states
     big = N * P * 4 > 8 * (1 << 30)
-    ema_buf = pop if big else pop.clone()      # EMA works on its own copy unless the population is huge
+    # the EMA works on the population itself when that is huge or was placed (so that the placed buffer is
+    # what is timed), else on a copy of its own
+    ema_buf = pop if (big or placed is not None) else pop.clone()
     out = torch.empty(P, dtype=torch.float32, device=dev)
     cnt = torch.zeros(1, dtype=torch.int64, device=dev)
     torch.cuda.synchronize()
@@ -258,6 +263,7 @@ def run_config(torch, wash, cfg, steps, warmup, p_override=None, count=True, str
         "analysis_passes": extra,
         "placement": ({"tuned": place_info["tuned"], "arena_GiB": place_info["arena_bytes"] / 2**30,
                        "offsets_GiB": [o / 2**30 for o in place_info["offsets"]],
+                       "boundaries_GiB": [b / 2**30 for b in place_info.get("boundaries", [])],
                        "probes_ms": [[(o / 2**30, round(ms, 3)) for o, ms in t] for t in place_info["probes_ms"]]}
                       if place_info is not None else {"tuned": False}),
     }
