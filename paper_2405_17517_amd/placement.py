@@ -99,10 +99,10 @@ def place_population(N: int, P: int, nbuf: int = 1, segs=None, device: str = "cu
       boundaries     info["boundaries"] of an earlier call with the same arena size in this process: the
                      search for them is not repeated
     Returns (buffers, info); info holds the arena tensor (keep it alive as long as the buffers), the chosen
-    offsets, the boundaries found, and the probe times in ms of every candidate.  The buffers are placed one after the other: the
-    parameters where they alone are fastest, then each further buffer where the pass over all buffers
-    placed so far is fastest.  Populations too small to matter (below 512 MiB per buffer) and arenas without
-    room to move are placed back to back without probing."""
+    offsets, the boundaries found, and the probe times in ms of every candidate.  The buffers are placed one
+    after the other: the parameters where they alone are fastest, then each further buffer where the pass
+    over all buffers placed so far is fastest.  Populations too small to matter (below 512 MiB per buffer)
+    and arenas without room to move are placed back to back without probing."""
     dev = torch.device(device)
     buf_bytes = N * P * 4
     pitch = (buf_bytes + 255) // 256 * 256
