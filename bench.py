@@ -385,7 +385,7 @@ def cpu_baseline_full(cfg, budget_s=3.0, mt_budget_s=0.5):
         "value": _r(cfg.P * passes / parts["wash_shuffle"], 5), "unit": "coords/s", "cores": 1, "kind": "oracle",
         "sample": f"{passes} whole passes over the full config-{cfg.index} population, {t_spent:.1f} s of CPU time",
         "us_per_call": {k: round(v / passes * 1e6, 1) for k, v in parts.items()},
-        "shuffle_all_cores": {"threads": threads, "us_per_call": round(mt_spent / mt_calls * 1e6, 1),
+        "all_cores": {"threads": threads, "us_per_call": round(mt_spent / mt_calls * 1e6, 1),
                               "coords_per_s": _r(cfg.P * mt_calls / mt_spent, 5)},
         "host_cores_available": os.cpu_count(),
     }
@@ -434,11 +434,9 @@ def cpu_baseline_sampled(cfg, steps=3, nsample=3):
     return {
         "value": _r(coords / parts["wash_shuffle"], 5), "unit": "coords/s", "cores": 1, "kind": "oracle",
         "sample": f"{len(sample_segments)} of {len(segs)} segments ({coords // steps} coordinates x {cfg.N} rows, "
-                  f"params{'+momentum' if cfg.momentum else ''}) x {steps} steps, {total:.1f} s CPU; "
-                  "ms per call extrapolated to the whole row",
+                  f"params{'+momentum' if cfg.momentum else ''}) x {steps} steps, {total:.1f} s CPU",
         "extrapolated_ms_per_call": {k: round(v * scale * 1e3) for k, v in parts.items()},
-        "shuffle_all_cores": {"threads": threads, "coords_per_s": _r(mt_coords / mt_spent, 5)},
-        "host_cores_available": os.cpu_count(),
+        "all_cores": {"threads": threads, "coords_per_s": _r(mt_coords / mt_spent, 4)},
     }
 
 
@@ -655,7 +653,7 @@ def main():
                 per_cfg[f"config{c.index}"] = cpu if c.index == cfg.index else cpu_baseline(c)
                 b = per_cfg[f"config{c.index}"]
                 note(f"oracle, config {c.index}: {b['value']:.3g} coords/s (1 core), "
-                     f"{b['shuffle_all_cores']['coords_per_s']:.3g} coords/s ({b['shuffle_all_cores']['threads']} threads)")
+                     f"{b['all_cores']['coords_per_s']:.3g} coords/s ({b['all_cores']['threads']} threads)")
             detail["cpu_baseline_per_config"] = per_cfg
 
     detail["placement_found"] = {str(k): v for k, v in _PLACEMENT.items()}
