@@ -27,7 +27,10 @@
  *     streams under graph capture, which cannot allocate), on first use;
  *     wash_shutdown() releases them.  Calls on different streams never share
  *     a workspace; wash_consensus_sqdist_noalloc is the one call that uses a
- *     fixed array instead.
+ *     fixed array instead.  At most 256 workspaces exist: when a process has
+ *     used more streams than that, the call that needs another one waits for
+ *     the device to become idle and takes back those of ordinary streams
+ *     (workspaces recorded into graphs stay with their graphs).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls enqueue work on it and return without waiting; the usual stream
  *     ordering applies to the buffers.

@@ -236,12 +236,27 @@ int get_workspace(int device, hipStream_t stream, bool need, void **out)
             if (capturing)
                 return fail(WASH_EHIP, "no workspace is set aside for this capture (device memory cannot be allocated while "
                                        "a stream captures): make one call of the library on this device outside the capture first");
-            if (g_workspaces.size() >= kMaxWorkspaces)
-                return fail(WASH_ENOMEM, "more than %zu streams and captures have used the library", kMaxWorkspaces);
-            Workspace *fresh = nullptr;
-            if (int rc = new_workspace(device, &fresh)) return rc;
-            spare_index = g_workspaces.size() - 1;
-            ++spares;
+            if (g_workspaces.size() >= kMaxWorkspaces) {
+                // Every workspace is taken (a long-lived process that keeps making streams).  Once the device is
+                // idle no launched kernel uses any of them and their ticket words are zero again, so those of
+                // ordinary streams go back to the pool; the ones recorded into graphs stay with their graphs.
+                const hipError_t e = hipDeviceSynchronize();
+                if (e != hipSuccess) return fail_hip("hipDeviceSynchronize(workspace pool)", e);
+                for (size_t k = 0; k < g_workspaces.size(); ++k) {
+                    Workspace &w = g_workspaces[k];
+                    if (w.device != device || !w.assigned || w.capture) continue;
+                    w.assigned = false;
+                    spare_index = k;
+                    ++spares;
+                }
+                if (spare_index == g_workspaces.size())
+                    return fail(WASH_ENOMEM, "all %zu workspaces belong to captured graphs or other devices", kMaxWorkspaces);
+            } else {
+                Workspace *fresh = nullptr;
+                if (int rc = new_workspace(device, &fresh)) return rc;
+                spare_index = g_workspaces.size() - 1;
+                ++spares;
+            }
         }
         Workspace &w = g_workspaces[spare_index];
         w.assigned = true;

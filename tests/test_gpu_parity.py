@@ -318,6 +318,39 @@ def test_host_threads_on_their_own_streams(wash):
         assert np.array_equal(_bits(final), _bits(ref)), k
 
 
+def test_more_streams_than_workspaces(wash):
+    """A process that keeps making streams: beyond 256 workspaces the library waits for the device and takes
+    the workspaces of ordinary streams back.  Every call still reports the oracle's count, also on streams
+    that held a workspace before the pool was recycled."""
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    N, P, nstreams = 4, 20_011, 300
+    pop = distinct_population(N, P)
+    segs = [(0, P, 0.1)]
+    want = [oracle.shuffle(pop.copy(), None, segs, 21, step) for step in range(3)]
+    d = torch.from_numpy(pop).cuda()
+    handles = []
+    for _ in range(nstreams):
+        h = ctypes.c_void_p()
+        assert hip.hipStreamCreate(ctypes.byref(h)) == 0
+        handles.append(h)
+    assert len({h.value for h in handles}) == nstreams
+    print("many streams", flush=True)
+    cnts = torch.zeros(nstreams, dtype=torch.int64, device="cuda")
+    works = [d.clone() for _ in range(nstreams)]
+    torch.cuda.synchronize()
+    again = (0, 1, 2, 150, nstreams - 1)              # these streams call once more after the pool was recycled
+    for k in list(range(nstreams)) + list(again):
+        with torch.cuda.stream(torch.cuda.ExternalStream(handles[k].value)):
+            wash.wash_shuffle(works[k], None, segs, 21, k % 3, cnts[k:k + 1])
+    torch.cuda.synchronize()
+    got = cnts.cpu().numpy()
+    for h in handles:
+        assert hip.hipStreamDestroy(h) == 0
+    for k in range(nstreams):
+        assert got[k] == want[k % 3] * (2 if k in again else 1), k
+
+
 def test_error_paths_launch_nothing(wash):
     d = torch.zeros((2, 100), dtype=torch.float32, device="cuda")
     d.copy_(torch.arange(200, dtype=torch.float32, device="cuda").view(2, 100))
