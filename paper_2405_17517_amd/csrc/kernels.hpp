@@ -35,7 +35,7 @@ struct ShuffleArgs {
     uint32_t key_lo, key_hi;    // seed
     uint32_t step;              // used when step_ptr is nullptr
     const unsigned long long *step_ptr; // device step counter read by the kernel (its low 32 bits), or nullptr
-    unsigned long long *step_advance;   // if set, incremented by one after the shuffle (by the kernel that follows it)
+    unsigned long long *step_advance;   // if set, incremented by one by the wavefront that ends the kernel (see tickets)
     unsigned long long *selected_count; // caller's counter, or nullptr
     // End-of-kernel bookkeeping (selected count, step advance) without a second launch: every active wavefront
     // adds (1 << 40 | its count) to one of kCountSlots ticket words; the wavefront that completes a word carries
