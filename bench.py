@@ -659,11 +659,12 @@ def main():
     detail["placement_found"] = {str(k): v for k, v in _PLACEMENT.items()}
     if args.detail:
         try:
-            os.makedirs(os.path.dirname(args.detail), exist_ok=True)
+            if os.path.dirname(args.detail):
+                os.makedirs(os.path.dirname(args.detail), exist_ok=True)
             with open(args.detail, "w") as f:
                 json.dump(detail, f, indent=1)
             line["detail_file"] = os.path.relpath(args.detail, ROOT)
-        except OSError as exc:
+        except (OSError, TypeError, ValueError) as exc:
             note(f"detail file not written: {exc}")
 
     sys.stderr.flush()
