@@ -549,10 +549,15 @@ def main():
     # (not under --placement-from: a traced run must hold the launches of one placement only)
     plain_res = None
     if main_res["placement"]["tuned"] and not args.placement_from:
-        plain_res = run_config(torch, wash, cfg, args.steps, args.warmup, p_override=args.p, count=not args.no_count,
-                               stream=args.stream, states=args.states, placement="default")
-        note(f"config {cfg.index}, allocator's placement: shuffle {plain_res['avg_us']['wash_shuffle']:.1f} us, ema "
-             f"{plain_res['avg_us']['papa_ema']:.1f} us, average {plain_res['avg_us']['wash_average']:.1f} us")
+        try:
+            plain_res = run_config(torch, wash, cfg, args.steps, args.warmup, p_override=args.p, count=not args.no_count,
+                                   stream=args.stream, states=args.states, placement="default")
+            note(f"config {cfg.index}, allocator's placement: shuffle {plain_res['avg_us']['wash_shuffle']:.1f} us, ema "
+                 f"{plain_res['avg_us']['papa_ema']:.1f} us, average {plain_res['avg_us']['wash_average']:.1f} us")
+        except (MemoryError, RuntimeError) as exc:                  # the headline does not depend on this run
+            note(f"run at the allocator's placement skipped: {exc}")
+            plain_res = None
+            torch.cuda.empty_cache()
     yard = copy_yardstick(torch, wash)
     scat = scatter_yardstick(torch, wash)
 
@@ -615,46 +620,12 @@ def main():
 
     default_run = (args.p is None and args.stream == "v1" and args.states is None)
     if not args.headline_only and default_run:
-        rows = []
-        for c in CONFIGS:
-            ps = c.p_sweep if c.p_sweep else (None,)
-            for p in ps:
-                k = max(5, min(c.steps, 20))
-                for st in ("v1", "gap"):
-                    if c.index == cfg.index and st == args.stream:
-                        res = dict(main_res)
-                    else:
-                        res = run_config(torch, wash, c, k, min(args.warmup, 3), p_override=p, stream=st,
-                                         placement=args.placement)
-                    res["p_override"] = p
-                    is_dense = st == "v1" and (p if p is not None else 0.0) >= 0.08
-                    res["roofline"]["wash_shuffle"]["bound"] = bound_label(c.N, res["buffers_shuffled"],
-                                                                           res["expected_fraction"], st, is_dense)
-                    res["shuffle_vs_scattered_stores_frac"] = (res["shuffle_store_units_per_s"]
-                                                               / (scat["stores_Gelem_per_s"] * 1e9))
-                    rows.append(res)
-                    note(f"config {c.index} p={p} stream {st}: shuffle {res['avg_us']['wash_shuffle']:.1f} us "
-                         f"({res['roofline']['wash_shuffle']['frac'] * 100:.2f} % of 2pNP4/t, "
-                         f"{res['roofline']['wash_shuffle']['bound']}-bound), ema {res['avg_us']['papa_ema']:.1f} us "
-                         f"({res['roofline']['papa_ema']['frac'] * 100:.1f} %), average "
-                         f"{res['avg_us']['wash_average']:.1f} us ({res['roofline']['wash_average']['frac'] * 100:.1f} %)")
-        detail["all_configs"] = rows
-        detail["rows_padded_to_128_bytes"] = {}
-        for c in CONFIGS:
-            if c.P % 32 != 0 and c.N * c.P * 4 >= (256 << 20):
-                r = padded_rows(torch, wash, c)
-                detail["rows_padded_to_128_bytes"][f"config{c.index}"] = r
-                note(f"config {c.index} with rows padded to 128 bytes: ema {r['papa_ema']['avg_us']:.1f} us "
-                     f"({r['papa_ema']['frac'] * 100:.1f} %), average {r['wash_average']['avg_us']:.1f} us "
-                     f"({r['wash_average']['frac'] * 100:.1f} %)")
-        if not args.no_cpu_baseline:
-            per_cfg = {}
-            for c in CONFIGS:
-                per_cfg[f"config{c.index}"] = cpu if c.index == cfg.index else cpu_baseline(c)
-                b = per_cfg[f"config{c.index}"]
-                note(f"oracle, config {c.index}: {b['value']:.3g} coords/s (1 core), "
-                     f"{b['all_cores']['coords_per_s']:.3g} coords/s ({b['all_cores']['threads']} threads)")
-            detail["cpu_baseline_per_config"] = per_cfg
+        # everything below goes to the detail file only: a failure there must not cost the headline line
+        try:
+            all_configs_detail(torch, wash, args, cfg, main_res, scat, cpu, detail, note)
+        except Exception as exc:                                    # noqa: BLE001
+            note(f"detail run stopped: {type(exc).__name__}: {exc}")
+            detail["detail_error"] = f"{type(exc).__name__}: {exc}"
 
     detail["placement_found"] = {str(k): v for k, v in _PLACEMENT.items()}
     if args.detail:
@@ -669,6 +640,52 @@ def main():
 
     sys.stderr.flush()
     print(json.dumps(line, separators=(",", ":")), flush=True)
+
+
+def all_configs_detail(torch, wash, args, cfg, main_res, scat, cpu, detail, note):
+    """Every other configuration with both mask streams, the streaming kernels on padded rows, and the oracle
+    timed per configuration: results go into `detail`."""
+    from workloads import CONFIGS
+    rows = []
+    for c in CONFIGS:
+        ps = c.p_sweep if c.p_sweep else (None,)
+        for p in ps:
+            k = max(5, min(c.steps, 20))
+            for st in ("v1", "gap"):
+                if c.index == cfg.index and st == args.stream:
+                    res = dict(main_res)
+                else:
+                    res = run_config(torch, wash, c, k, min(args.warmup, 3), p_override=p, stream=st,
+                                     placement=args.placement)
+                res["p_override"] = p
+                is_dense = st == "v1" and (p if p is not None else 0.0) >= 0.08
+                res["roofline"]["wash_shuffle"]["bound"] = bound_label(c.N, res["buffers_shuffled"],
+                                                                       res["expected_fraction"], st, is_dense)
+                res["shuffle_vs_scattered_stores_frac"] = (res["shuffle_store_units_per_s"]
+                                                           / (scat["stores_Gelem_per_s"] * 1e9))
+                rows.append(res)
+                note(f"config {c.index} p={p} stream {st}: shuffle {res['avg_us']['wash_shuffle']:.1f} us "
+                     f"({res['roofline']['wash_shuffle']['frac'] * 100:.2f} % of 2pNP4/t, "
+                     f"{res['roofline']['wash_shuffle']['bound']}-bound), ema {res['avg_us']['papa_ema']:.1f} us "
+                     f"({res['roofline']['papa_ema']['frac'] * 100:.1f} %), average "
+                     f"{res['avg_us']['wash_average']:.1f} us ({res['roofline']['wash_average']['frac'] * 100:.1f} %)")
+    detail["all_configs"] = rows
+    detail["rows_padded_to_128_bytes"] = {}
+    for c in CONFIGS:
+        if c.P % 32 != 0 and c.N * c.P * 4 >= (256 << 20):
+            r = padded_rows(torch, wash, c)
+            detail["rows_padded_to_128_bytes"][f"config{c.index}"] = r
+            note(f"config {c.index} with rows padded to 128 bytes: ema {r['papa_ema']['avg_us']:.1f} us "
+                 f"({r['papa_ema']['frac'] * 100:.1f} %), average {r['wash_average']['avg_us']:.1f} us "
+                 f"({r['wash_average']['frac'] * 100:.1f} %)")
+    if not args.no_cpu_baseline:
+        per_cfg = {}
+        for c in CONFIGS:
+            per_cfg[f"config{c.index}"] = cpu if c.index == cfg.index else cpu_baseline(c)
+            b = per_cfg[f"config{c.index}"]
+            note(f"oracle, config {c.index}: {b['value']:.3g} coords/s (1 core), "
+                 f"{b['all_cores']['coords_per_s']:.3g} coords/s ({b['all_cores']['threads']} threads)")
+        detail["cpu_baseline_per_config"] = per_cfg
 
 
 if __name__ == "__main__":
